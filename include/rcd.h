@@ -1,0 +1,155 @@
+/*
+ * rcd.h - C ABI of the MI355X (gfx950) implementation of the ratio-constrained
+ * submodular partitioner of RCD-SGD (arXiv 2211.00839, Algorithm 1, with the
+ * facility-location function and Gaussian-kernel similarity of Section 4).
+ *
+ * Conventions for every entry point
+ *   - `*_dev` arguments are device pointers (HIP global memory on the current
+ *     device), `*_host` arguments are host pointers.  The caller owns every
+ *     buffer, workspace included; the library keeps no pointer after a call
+ *     returns, allocates no device memory and frees nothing.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   - Inputs are never modified.  The return value is an rcd_status; on any
+ *     value other than RCD_OK the contents of output buffers are unspecified.
+ *     Arguments are validated before the first launch.  No exception or abort
+ *     crosses the boundary.
+ *   - Same inputs give byte-identical outputs (fixed reduction orders, no
+ *     floating-point atomics).
+ *   - "lowest index" always means the lowest position in the caller's arrays.
+ *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
+ */
+#ifndef RCD_H
+#define RCD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RCD_MAX_K 16 /* largest number of workers (blocks) supported */
+
+typedef enum {
+    RCD_OK = 0,
+    RCD_ERR_INVALID_ARG = 1,  /* null pointer, non-positive size, bad leading dimension, sigma2 <= 0 */
+    RCD_ERR_BAD_LABEL = 2,    /* a label outside [0, L) */
+    RCD_ERR_BAD_CAPACITY = 3, /* capacity < 1 (data set) / quota < 0 or sum of quotas > n (class) */
+    RCD_ERR_UNSUPPORTED = 4,  /* K > RCD_MAX_K, unknown dtype or mode, size beyond 2^31-1 */
+    RCD_ERR_WORKSPACE = 5,    /* workspace pointer null/misaligned or smaller than required */
+    RCD_ERR_HIP = 6,          /* a HIP call failed; rcd_last_hip_error() has its text */
+    RCD_ERR_BAD_SIMILARITY = 7 /* a similarity outside [0, 1] (or NaN) was found in a caller-supplied S */
+} rcd_status;
+
+typedef enum { RCD_F32 = 0, RCD_BF16 = 1 } rcd_dtype;
+
+typedef enum {
+    RCD_MODE_AUTO = 0,     /* stored if the workspace can hold at least one class's S, else recompute */
+    RCD_MODE_STORED = 1,   /* build S per class once, stream it in every gain sweep */
+    RCD_MODE_RECOMPUTE = 2 /* never store S: rebuild its tiles from X inside every gain sweep */
+} rcd_mode;
+
+/*
+ * Similarity build.  Section 4 ("Gaussian kernel with L2 distance"):
+ *     S[i*ld_s + j] = exp(-||x_i - x_j||^2 / (2*sigma2)),   0 <= i,j < n,
+ * x_i = row i of X (n x d, leading dimension ld_x, dtype dt).  The squared
+ * distance comes from the Gram matrix X X^T (matrix cores, fp32 accumulation)
+ * and the squared row norms, clamped at 0; S is exactly symmetric and its
+ * diagonal is exactly 1.0f.  row_index_dev (nullable, int32[n]) selects rows:
+ * x_i = row row_index_dev[i] of X.  Asynchronous on `stream`.
+ * Requirements: d >= 1, ld_x >= d, ld_s >= n.  Fastest when X is 16-byte aligned
+ * and ld_x * sizeof(element) is a multiple of 16.
+ * workspace: rcd_similarity_workspace_bytes(n) bytes (the squared row norms).
+ */
+int rcd_similarity(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x,
+                   const int32_t *row_index_dev, float sigma2, float *S_dev, int64_t ld_s,
+                   void *workspace_dev, size_t workspace_bytes, void *stream);
+size_t rcd_similarity_workspace_bytes(int64_t n);
+
+/*
+ * Quota rule.  Algorithm 1, constraint line: C_{l,j} = n_l * r_j / sum_j r_j,
+ * made integral by floor; the remainder goes one each to the workers with the
+ * largest r (lowest index first among equals), the same workers in every class.
+ * Host only.  r_host[K] >= 1, cap_host[K] receives the quotas (sum = n_l).
+ */
+int rcd_quota(int64_t n_l, const int32_t *r_host, int K, int64_t *cap_host);
+
+/*
+ * One gain sweep (the GreedyStep of Algorithm 1 evaluated for every candidate
+ * and every block at once, facility-location f of Section 4):
+ *     gains[k*n + v] = sum_{j<n} max(0, S[j*ld_s + v] - cur[k*n + j])
+ * for all k < K, v < n, accumulated in fp32 in a fixed order.  S must be
+ * symmetric with entries in [0,1]; cur_dev is K x n (coverage vectors).
+ * Exposed so that the kernel can be checked and timed on its own; the
+ * partition entry points run the same kernel on their internal state.
+ * Synchronises `stream` before returning.
+ */
+int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const float *cur_dev,
+                   float *gains_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/*
+ * One class of Algorithm 1 (its inner while loop):
+ *   repeat until every quota is met: j* = the non-full block with the least
+ *   f (lowest index on ties); v* = the unassigned sample with the largest
+ *   f(A_j* u {v}) - f(A_j*) (lowest index on ties); give v* to j*.
+ * Similarity source: S_dev (n x n, ld_s, symmetric, entries in [0,1]) if it is
+ * non-null, otherwise X_dev/dt/d/ld_x/sigma2 and S is recomputed tile by tile
+ * inside every sweep (never stored).
+ *   cap_host[K]   quotas, each >= 0, sum <= n
+ *   assign_dev[n] block of each sample, -1 if left over (sum of quotas < n)
+ *   order_dev[n]  (nullable) step at which the sample was taken, -1 if never
+ *   obj_host[K]   f(A_k) of the final blocks, evaluated from the coverage
+ *                 vectors in double precision
+ * Synchronises `stream` before returning.
+ */
+int rcd_partition_class(const float *S_dev, int64_t ld_s,
+                        const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
+                        int64_t n, int K, const int64_t *cap_host,
+                        int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                        void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/*
+ * Whole data set (Algorithm 1, outer loop): split the samples by label keeping
+ * their order, give every class the quotas of rcd_quota, run the class greedy
+ * on every class (classes are advanced together, as many at a time as the
+ * workspace holds), and join the per-class blocks.
+ *   labels_dev[N] in [0, L);  r_host[K] integer capacities >= 1
+ *   assign_dev[N] worker of each sample;  order_dev[N] (nullable) step index
+ *   inside the sample's own class;  obj_host[L*K] row-major f(A_k^l).
+ * Synchronises `stream` before returning.
+ */
+int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
+                          const int32_t *labels_dev, int L, const int32_t *r_host, int K,
+                          float sigma2, int mode,
+                          int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                          void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Workspace sizes in bytes (multiples of 256; the pointer must be 256-byte aligned).
+ * rcd_class_workspace_bytes: what rcd_partition_class / rcd_gain_sweep need for a
+ *   class of n samples (stored mode includes a private n x ld copy of S).
+ * rcd_dataset_workspace_bytes: `min` is enough to run one class of max_class_n at
+ *   a time, `full` lets all L classes advance together (fastest). */
+size_t rcd_class_workspace_bytes(int64_t n, int K, int mode);
+int rcd_dataset_workspace_bytes(int64_t N, int L, int64_t max_class_n, int K, int mode,
+                                size_t *min_bytes, size_t *full_bytes);
+
+/* Static description of a status code. */
+const char *rcd_strerror(int status);
+/* Text of the HIP error behind the calling thread's last RCD_ERR_HIP ("" if none). */
+const char *rcd_last_hip_error(void);
+
+/*
+ * Counters of the calling thread's last partition call (for benchmarks):
+ *   out[0] greedy steps taken        out[1] gain sweeps that did work
+ *   out[2] sum over those sweeps of (candidates x class size) = similarity
+ *          entries streamed          out[3] sum over steps of candidates
+ *          (gain evaluations Algorithm 1 consumes)
+ *   out[4] kernel launches           out[5] sum over sweeps of blocks evaluated
+ *          x candidates (gain evaluations computed)
+ */
+void rcd_last_stats(int64_t *out6_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RCD_H */

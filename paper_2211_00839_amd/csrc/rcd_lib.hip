@@ -1,0 +1,588 @@
+// Host side of librcd: argument checks, workspace layout, class grouping and the
+// round loop that drives the kernels.  One translation unit: the kernel files
+// are included so that their launch stubs are local to this library.
+#include <hip/hip_runtime.h>
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "../../include/rcd.h"
+#include "rcd_state.h"
+#include "greedy_kernels.hip"
+#include "similarity_kernels.hip"
+#include "split_kernels.hip"
+
+static_assert(RCD_KMAX == RCD_MAX_K, "public and internal block limits differ");
+
+namespace {
+
+thread_local char g_hip_err[320] = "";
+thread_local int64_t g_stats[6] = {0, 0, 0, 0, 0, 0};
+thread_local RcdPlan *g_pinned = nullptr;   // 2 progress slots, pinned, never freed
+
+#define HIP_TRY(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess) {                                                            \
+            snprintf(g_hip_err, sizeof g_hip_err, "%s -> %s", #expr, hipGetErrorString(e_)); \
+            return RCD_ERR_HIP;                                                            \
+        }                                                                                  \
+    } while (0)
+
+#define RCD_TRY(expr)              \
+    do {                           \
+        int rc_ = (expr);          \
+        if (rc_ != RCD_OK) return rc_; \
+    } while (0)
+
+inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int pitch_of(int64_t n) { return (int)((std::max<int64_t>(n, 1) + RCD_TILE - 1) / RCD_TILE * RCD_TILE); }
+
+int env_int(const char *name, int dflt, int lo, int hi)
+{
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    long v = strtol(s, nullptr, 10);
+    if (v < lo) v = lo;
+    if (v > hi) v = hi;
+    return (int)v;
+}
+
+struct Carver {
+    char *base;
+    size_t off, cap;
+    bool fail;
+    Carver(void *p, size_t bytes) : base((char *)p), off(0), cap(bytes), fail(false) {}
+    template <typename T> T *take(size_t count)
+    {
+        const size_t b = up256(count * sizeof(T));
+        if (off + b > cap) { fail = true; return nullptr; }
+        T *p = reinterpret_cast<T *>(base + off);
+        off += b;
+        return p;
+    }
+};
+
+size_t class_state_bytes(int64_t n, int K, bool stored)
+{
+    const size_t ld = (size_t)pitch_of(n);
+    size_t b = 0;
+    if (stored) b += up256((size_t)n * ld * 4);
+    b += up256((size_t)K * ld * 4);              // cur
+    b += up256((size_t)RCD_CMAX * K * ld * 4);   // part
+    b += up256((size_t)K * ld * 4);              // gain
+    b += up256(ld * 4);                          // perm
+    return b;
+}
+
+size_t group_fixed_bytes(int ncls, int K)
+{
+    return up256((size_t)ncls * sizeof(RcdClass)) + up256(sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4) +
+           up256((size_t)ncls * K * sizeof(double));
+}
+
+struct Group {
+    RcdClass *classes_dev = nullptr;
+    RcdPlan *plan_dev = nullptr;
+    double *obj_dev = nullptr;
+    std::vector<RcdClass> host;   // kept alive until the stream has consumed it
+    int K = 0;
+};
+
+// Carve the state of one class out of the workspace and fill its descriptor.
+bool carve_class(Carver &cv, RcdClass &c, int64_t n, int K, const int64_t *cap, bool stored)
+{
+    memset(&c, 0, sizeof c);
+    const size_t ld = (size_t)pitch_of(n);
+    c.n = (int)n;
+    c.ld = (int)ld;
+    c.K = K;
+    if (stored) c.M = cv.take<float>((size_t)n * ld);
+    c.cur = cv.take<float>((size_t)K * ld);
+    c.part = cv.take<float>((size_t)RCD_CMAX * K * ld);
+    c.gain = cv.take<float>((size_t)K * ld);
+    c.perm = cv.take<int32_t>(ld);
+    int64_t total = 0;
+    for (int k = 0; k < K; ++k) {
+        c.cap[k] = (int)cap[k];
+        total += cap[k];
+    }
+    c.total = (int)total;
+    c.nR = (int)n;
+    c.mode = stored ? RCD_MODE_STORED : RCD_MODE_RECOMPUTE;
+    return !cv.fail;
+}
+
+int sweep_items_bound(const RcdClass &c)
+{
+    const int tiles0 = (c.n + RCD_TILE - 1) / RCD_TILE;
+    return std::min(RCD_CMAX * tiles0, c.target_items + tiles0);
+}
+
+void choose_chunks(int n, int nR, int target_items, int *C, int *rpc)
+{
+    const int tiles = (nR + RCD_TILE - 1) / RCD_TILE;
+    int c = (target_items + tiles - 1) / tiles;
+    c = c < 1 ? 1 : (c > RCD_CMAX ? RCD_CMAX : c);
+    int r = (n + c - 1) / c;
+    r = (r + 15) & ~15;
+    *rpc = r;
+    *C = (n + r - 1) / r;
+}
+
+int ensure_pinned()
+{
+    if (!g_pinned) {
+        void *p = nullptr;
+        HIP_TRY(hipHostMalloc(&p, 2 * sizeof(RcdPlan), hipHostMallocDefault));
+        g_pinned = (RcdPlan *)p;
+    }
+    return RCD_OK;
+}
+
+// Upload the descriptors, reset the state and run rounds until every class of
+// the group is finished.  Fills g.obj_dev.  Accumulates g_stats.
+int run_group(Group &g, hipStream_t stream)
+{
+    const int ncls = (int)g.host.size();
+    RCD_TRY(ensure_pinned());
+    const int target_total = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
+    const int per_class = std::max(1, target_total / ncls);
+    int items_ub = 0, tiles_ub = 0;
+    for (RcdClass &c : g.host) {
+        c.target_items = per_class;
+        items_ub += sweep_items_bound(c);
+        tiles_ub += (c.n + RCD_TILE - 1) / RCD_TILE;
+    }
+    RcdPlan plan0;
+    memset(&plan0, 0, sizeof plan0);
+    plan0.ncls = ncls;
+    // the validation kernels may already have raised plan->bad: keep it
+    HIP_TRY(hipMemcpyAsync(&g.plan_dev->ncls, &plan0.ncls, sizeof(int32_t) * 5, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(g.classes_dev, g.host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(rcd_k_init, dim3(64, ncls), dim3(256), 0, stream, g.classes_dev);
+
+    hipEvent_t ev[2];
+    HIP_TRY(hipEventCreateWithFlags(&ev[0], hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&ev[1], hipEventDisableTiming));
+    const int rounds = env_int("RCD_ROUNDS_PER_BATCH", 16, 1, 1024);
+    int64_t launches = 1;
+    int rc = RCD_OK;
+    // every round takes at least one step in every unfinished class, so this
+    // many batches always suffice; running past it means a defect, not work
+    int64_t max_total = 0;
+    for (const RcdClass &c : g.host) max_total = std::max<int64_t>(max_total, c.total);
+    const int64_t max_batches = (max_total + 2) / rounds + 3;
+    for (int64_t b = 0;; ++b) {
+        if (b > max_batches) {
+            snprintf(g_hip_err, sizeof g_hip_err, "greedy made no progress within %lld batches", (long long)max_batches);
+            rc = RCD_ERR_HIP;
+            break;
+        }
+        for (int r = 0; r < rounds; ++r) {
+            hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev,
+                               g.plan_dev, 0);
+            hipLaunchKernelGGL(rcd_k_sweep, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream,
+                               (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
+            hipLaunchKernelGGL(rcd_k_finalize, dim3(tiles_ub), dim3(RCD_TILE), 0, stream,
+                               (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
+        }
+        launches += 3 * (int64_t)rounds;
+        hipError_t le = hipGetLastError();
+        if (le != hipSuccess) {
+            snprintf(g_hip_err, sizeof g_hip_err, "kernel launch -> %s", hipGetErrorString(le));
+            rc = RCD_ERR_HIP;
+            break;
+        }
+        hipError_t e1 = hipMemcpyAsync(&g_pinned[b & 1], g.plan_dev, sizeof(RcdPlan), hipMemcpyDeviceToHost, stream);
+        hipError_t e2 = hipEventRecord(ev[b & 1], stream);
+        if (e1 != hipSuccess || e2 != hipSuccess) {
+            snprintf(g_hip_err, sizeof g_hip_err, "progress readback -> %s",
+                     hipGetErrorString(e1 != hipSuccess ? e1 : e2));
+            rc = RCD_ERR_HIP;
+            break;
+        }
+        if (b >= 1) {
+            hipError_t e3 = hipEventSynchronize(ev[(b - 1) & 1]);
+            if (e3 != hipSuccess) {
+                snprintf(g_hip_err, sizeof g_hip_err, "hipEventSynchronize -> %s", hipGetErrorString(e3));
+                rc = RCD_ERR_HIP;
+                break;
+            }
+            const RcdPlan &seen = g_pinned[(b - 1) & 1];
+            if (seen.bad) { rc = RCD_ERR_BAD_SIMILARITY; break; }
+            if (seen.ndone >= ncls) break;
+        }
+    }
+    hipError_t es = hipStreamSynchronize(stream);
+    hipEventDestroy(ev[0]);
+    hipEventDestroy(ev[1]);
+    if (rc != RCD_OK) return rc;
+    if (es != hipSuccess) {
+        snprintf(g_hip_err, sizeof g_hip_err, "hipStreamSynchronize -> %s", hipGetErrorString(es));
+        return RCD_ERR_HIP;
+    }
+    hipLaunchKernelGGL(rcd_k_objective, dim3(g.K, ncls), dim3(256), 0, stream, (const RcdClass *)g.classes_dev,
+                       g.obj_dev, g.K);
+    HIP_TRY(hipMemcpyAsync(g.host.data(), g.classes_dev, sizeof(RcdClass) * ncls, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    for (const RcdClass &c : g.host) {
+        g_stats[0] += c.stat_steps;
+        g_stats[1] += c.stat_sweeps;
+        g_stats[2] += c.stat_entries;
+        g_stats[3] += c.stat_useful;
+        g_stats[5] += c.stat_computed;
+    }
+    g_stats[4] += launches + 1;
+    return RCD_OK;
+}
+
+bool carve_group_fixed(Carver &cv, Group &g, int ncls, int K)
+{
+    g.classes_dev = cv.take<RcdClass>((size_t)ncls);
+    g.plan_dev = reinterpret_cast<RcdPlan *>(cv.take<char>(sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4));
+    g.obj_dev = cv.take<double>((size_t)ncls * K);
+    g.K = K;
+    return !cv.fail;
+}
+
+int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, const int32_t *row_index,
+                      float sigma2, float *S, int64_t ld_s, int ncols_pad, float *sq, hipStream_t stream)
+{
+    const float exp_scale = (float)(-1.4426950408889634 / (2.0 * (double)sigma2));
+    const dim3 grid((unsigned)((ncols_pad + sim::BN - 1) / sim::BN), (unsigned)((n + sim::BM - 1) / sim::BM));
+    const unsigned nblk = (unsigned)((n + 3) / 4);
+    if (dt == RCD_F32) {
+        hipLaunchKernelGGL(sim::k_row_norms<float>, dim3(nblk), dim3(256), 0, stream, (const float *)X,
+                           (long long)ldx, row_index, (int)n, (int)d, sq);
+        hipLaunchKernelGGL(sim::k_gram_rbf<float>, grid, dim3(sim::THREADS), 0, stream, (const float *)X,
+                           (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
+                           (long long)ld_s, ncols_pad);
+    } else {
+        hipLaunchKernelGGL(sim::k_row_norms<__bf16>, dim3(nblk), dim3(256), 0, stream, (const __bf16 *)X,
+                           (long long)ldx, row_index, (int)n, (int)d, sq);
+        hipLaunchKernelGGL(sim::k_gram_rbf<__bf16>, grid, dim3(sim::THREADS), 0, stream, (const __bf16 *)X,
+                           (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
+                           (long long)ld_s, ncols_pad);
+    }
+    HIP_TRY(hipGetLastError());
+    return RCD_OK;
+}
+
+int check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return RCD_OK;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0 || have < need) return RCD_ERR_WORKSPACE;
+    return RCD_OK;
+}
+
+int check_common(int64_t n, int K)
+{
+    if (n < 0) return RCD_ERR_INVALID_ARG;
+    if (K < 1) return RCD_ERR_INVALID_ARG;
+    if (K > RCD_MAX_K) return RCD_ERR_UNSUPPORTED;
+    if (n > (int64_t)0x7fffff00) return RCD_ERR_UNSUPPORTED;
+    return RCD_OK;
+}
+
+void reset_stats() { memset(g_stats, 0, sizeof g_stats); }
+
+} // namespace
+
+// ===========================================================================
+extern "C" {
+
+const char *rcd_strerror(int status)
+{
+    switch (status) {
+    case RCD_OK: return "ok";
+    case RCD_ERR_INVALID_ARG: return "invalid argument";
+    case RCD_ERR_BAD_LABEL: return "label outside [0, L)";
+    case RCD_ERR_BAD_CAPACITY: return "bad capacity or quota";
+    case RCD_ERR_UNSUPPORTED: return "unsupported size, dtype or mode";
+    case RCD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case RCD_ERR_HIP: return "HIP runtime error";
+    case RCD_ERR_BAD_SIMILARITY: return "similarity outside [0, 1]";
+    default: return "unknown status";
+    }
+}
+
+const char *rcd_last_hip_error(void) { return g_hip_err; }
+
+void rcd_last_stats(int64_t *out6_host)
+{
+    if (out6_host) memcpy(out6_host, g_stats, sizeof g_stats);
+}
+
+size_t rcd_similarity_workspace_bytes(int64_t n) { return n > 0 ? up256((size_t)n * 4) : 0; }
+
+int rcd_similarity(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x,
+                   const int32_t *row_index_dev, float sigma2, float *S_dev, int64_t ld_s,
+                   void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
+    if (n < 0 || d < 1 || ld_x < d || ld_s < n || !(sigma2 > 0.f) || !std::isfinite(sigma2)) return RCD_ERR_INVALID_ARG;
+    if (n > (int64_t)0x7fffff00 || d > (int64_t)0x7fffff00) return RCD_ERR_UNSUPPORTED;
+    if (n == 0) return RCD_OK;
+    if (!X_dev || !S_dev) return RCD_ERR_INVALID_ARG;
+    RCD_TRY(check_workspace(workspace_dev, workspace_bytes, rcd_similarity_workspace_bytes(n)));
+    return launch_similarity(X_dev, dt, n, d, ld_x, row_index_dev, sigma2, S_dev, ld_s, (int)n,
+                             (float *)workspace_dev, (hipStream_t)stream);
+}
+
+int rcd_quota(int64_t n_l, const int32_t *r_host, int K, int64_t *cap_host)
+{
+    if (n_l < 0 || K < 1 || !r_host || !cap_host) return RCD_ERR_INVALID_ARG;
+    int64_t R = 0;
+    for (int k = 0; k < K; ++k) {
+        if (r_host[k] < 1) return RCD_ERR_BAD_CAPACITY;
+        R += r_host[k];
+    }
+    int64_t given = 0;
+    for (int k = 0; k < K; ++k) {
+        // n_l * r_k fits in 128 bits trivially; keep to 64 by splitting the product
+        cap_host[k] = (int64_t)(((__int128)n_l * r_host[k]) / R);
+        given += cap_host[k];
+    }
+    // workers in the order (r descending, index ascending) receive the remainder
+    std::vector<int> order(K);
+    for (int k = 0; k < K; ++k) order[k] = k;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return r_host[a] > r_host[b]; });
+    int64_t rem = n_l - given;
+    for (int i = 0; i < K && rem > 0; ++i, --rem) cap_host[order[i]] += 1;
+    return RCD_OK;
+}
+
+size_t rcd_class_workspace_bytes(int64_t n, int K, int mode)
+{
+    if (n <= 0 || K < 1 || K > RCD_MAX_K) return 0;
+    const bool stored = mode != RCD_MODE_RECOMPUTE;
+    return group_fixed_bytes(1, K) + class_state_bytes(n, K, stored);
+}
+
+int rcd_dataset_workspace_bytes(int64_t N, int L, int64_t max_class_n, int K, int mode,
+                                size_t *min_bytes, size_t *full_bytes)
+{
+    if (N < 0 || L < 1 || K < 1 || max_class_n < 0 || max_class_n > N) return RCD_ERR_INVALID_ARG;
+    if (K > RCD_MAX_K) return RCD_ERR_UNSUPPORTED;
+    const bool stored = mode != RCD_MODE_RECOMPUTE;
+    const size_t nchunks = (size_t)((N + split::CHUNK - 1) / split::CHUNK);
+    const size_t fixed = up256((size_t)N * 4) + 2 * up256((size_t)L * 4) + up256(nchunks * L * 4) + up256(sizeof(RcdPlan));
+    const size_t one = class_state_bytes(max_class_n, K, stored) + up256((size_t)max_class_n * 4);
+    if (min_bytes) *min_bytes = fixed + group_fixed_bytes(1, K) + one;
+    // every class at most max_class_n and the sizes sum to N: the similarity
+    // matrices together need at most ceil(N / max) classes of the largest size
+    const size_t worst_classes = max_class_n > 0 ? (size_t)std::min<int64_t>(L, (N + max_class_n - 1) / max_class_n + 1) : 1;
+    if (full_bytes) {
+        size_t small = class_state_bytes(1, K, stored) + up256(4);
+        *full_bytes = fixed + group_fixed_bytes(L, K) + worst_classes * one + (size_t)L * small;
+    }
+    return RCD_OK;
+}
+
+int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const float *cur_dev,
+                   float *gains_dev, void *workspace_dev, size_t workspace_bytes, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    RCD_TRY(check_common(n, K));
+    if (n == 0) return RCD_OK;
+    if (!S_dev || !cur_dev || !gains_dev || ld_s < n) return RCD_ERR_INVALID_ARG;
+    RCD_TRY(check_workspace(workspace_dev, workspace_bytes, rcd_class_workspace_bytes(n, K, RCD_MODE_STORED)));
+    Carver cv(workspace_dev, workspace_bytes);
+    Group g;
+    if (!carve_group_fixed(cv, g, 1, K)) return RCD_ERR_WORKSPACE;
+    g.host.resize(1);
+    std::vector<int64_t> cap(K, 0);
+    RcdClass &c = g.host[0];
+    if (!carve_class(cv, c, n, K, cap.data(), true)) return RCD_ERR_WORKSPACE;
+    c.assign_out = nullptr;
+    c.nneed = K;
+    for (int k = 0; k < K; ++k) c.need[k] = k;
+    c.target_items = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
+    choose_chunks(c.n, c.nR, c.target_items, &c.C, &c.rpc);
+    const int tiles = (c.n + RCD_TILE - 1) / RCD_TILE;
+    struct { RcdPlan p; int32_t pre[4]; } plan;
+    memset(&plan, 0, sizeof plan);
+    plan.p.ncls = 1;
+    plan.p.items = tiles * c.C;
+    plan.p.tiles = tiles;
+    plan.pre[0] = 0; plan.pre[1] = plan.p.items; plan.pre[2] = 0; plan.pre[3] = tiles;
+    HIP_TRY(hipMemcpyAsync(g.plan_dev, &plan, sizeof plan, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(g.classes_dev, g.host.data(), sizeof(RcdClass), hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
+                       (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
+    hipLaunchKernelGGL(rcd_k_import_cur, dim3((unsigned)((n + 255) / 256), K), dim3(256), 0, stream,
+                       (const RcdClass *)g.classes_dev, cur_dev);
+    hipLaunchKernelGGL(rcd_k_sweep, dim3(plan.p.items), dim3(RCD_SWEEP_THREADS), 0, stream,
+                       (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
+    hipLaunchKernelGGL(rcd_k_finalize, dim3(tiles), dim3(RCD_TILE), 0, stream, (const RcdClass *)g.classes_dev,
+                       (const RcdPlan *)g.plan_dev);
+    hipLaunchKernelGGL(rcd_k_export_gains, dim3((unsigned)((n + 255) / 256), K), dim3(256), 0, stream,
+                       (const RcdClass *)g.classes_dev, gains_dev);
+    HIP_TRY(hipGetLastError());
+    RcdPlan back;
+    HIP_TRY(hipMemcpyAsync(&back, g.plan_dev, sizeof back, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (back.bad) return RCD_ERR_BAD_SIMILARITY;
+    return RCD_OK;
+}
+
+int rcd_partition_class(const float *S_dev, int64_t ld_s,
+                        const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
+                        int64_t n, int K, const int64_t *cap_host,
+                        int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                        void *workspace_dev, size_t workspace_bytes, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    reset_stats();
+    RCD_TRY(check_common(n, K));
+    if (!cap_host || !obj_host) return RCD_ERR_INVALID_ARG;
+    int64_t total = 0;
+    for (int k = 0; k < K; ++k) {
+        if (cap_host[k] < 0) return RCD_ERR_BAD_CAPACITY;
+        total += cap_host[k];
+    }
+    if (total > n) return RCD_ERR_BAD_CAPACITY;
+    for (int k = 0; k < K; ++k) obj_host[k] = 0.0;
+    if (n == 0) return RCD_OK;
+    if (!assign_dev) return RCD_ERR_INVALID_ARG;
+    const bool stored = S_dev != nullptr;
+    if (stored) {
+        if (ld_s < n) return RCD_ERR_INVALID_ARG;
+    } else {
+        if (!X_dev || d < 1 || ld_x < d || !(sigma2 > 0.f)) return RCD_ERR_INVALID_ARG;
+        if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
+        return RCD_ERR_UNSUPPORTED;   // recompute sweep: not built yet
+    }
+    RCD_TRY(check_workspace(workspace_dev, workspace_bytes,
+                            rcd_class_workspace_bytes(n, K, stored ? RCD_MODE_STORED : RCD_MODE_RECOMPUTE)));
+    Carver cv(workspace_dev, workspace_bytes);
+    Group g;
+    if (!carve_group_fixed(cv, g, 1, K)) return RCD_ERR_WORKSPACE;
+    g.host.resize(1);
+    RcdClass &c = g.host[0];
+    if (!carve_class(cv, c, n, K, cap_host, stored)) return RCD_ERR_WORKSPACE;
+    c.assign_out = assign_dev;
+    c.order_out = order_dev;
+    HIP_TRY(hipMemsetAsync(g.plan_dev, 0, sizeof(RcdPlan), stream));
+    hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
+                       (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
+    RCD_TRY(run_group(g, stream));
+    HIP_TRY(hipMemcpy(obj_host, g.obj_dev, sizeof(double) * K, hipMemcpyDeviceToHost));
+    return RCD_OK;
+}
+
+int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
+                          const int32_t *labels_dev, int L, const int32_t *r_host, int K,
+                          float sigma2, int mode,
+                          int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                          void *workspace_dev, size_t workspace_bytes, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    reset_stats();
+    RCD_TRY(check_common(N, K));
+    if (L < 1 || !r_host || !obj_host) return RCD_ERR_INVALID_ARG;
+    if (L > 8192) return RCD_ERR_UNSUPPORTED;
+    if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
+    if (mode != RCD_MODE_AUTO && mode != RCD_MODE_STORED && mode != RCD_MODE_RECOMPUTE) return RCD_ERR_UNSUPPORTED;
+    if (d < 1 || ld_x < d || !(sigma2 > 0.f) || !std::isfinite(sigma2)) return RCD_ERR_INVALID_ARG;
+    for (int k = 0; k < K; ++k)
+        if (r_host[k] < 1) return RCD_ERR_BAD_CAPACITY;
+    for (size_t i = 0; i < (size_t)L * K; ++i) obj_host[i] = 0.0;
+    if (N == 0) return RCD_OK;
+    if (!X_dev || !labels_dev || !assign_dev) return RCD_ERR_INVALID_ARG;
+    if (mode == RCD_MODE_RECOMPUTE) return RCD_ERR_UNSUPPORTED;   // recompute sweep: not built yet
+
+    // ---- class split (stable counting sort of indices by label)
+    const int nchunks = (int)((N + split::CHUNK - 1) / split::CHUNK);
+    Carver cv(workspace_dev, workspace_bytes);
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) != 0) return RCD_ERR_WORKSPACE;
+    int32_t *idx = cv.take<int32_t>((size_t)N);
+    int32_t *class_count = cv.take<int32_t>((size_t)L);
+    int32_t *class_offset = cv.take<int32_t>((size_t)L);
+    int32_t *chunk_hist = cv.take<int32_t>((size_t)nchunks * L);
+    RcdPlan *flag = reinterpret_cast<RcdPlan *>(cv.take<char>(sizeof(RcdPlan)));
+    if (cv.fail) return RCD_ERR_WORKSPACE;
+    HIP_TRY(hipMemsetAsync(flag, 0, sizeof(RcdPlan), stream));
+    hipLaunchKernelGGL(split::k_hist, dim3(nchunks), dim3(64), (size_t)L * 4, stream, labels_dev, (long long)N, L,
+                       chunk_hist, flag);
+    hipLaunchKernelGGL(split::k_scan, dim3((L + 255) / 256), dim3(256), 0, stream, chunk_hist, nchunks, L,
+                       class_count);
+    HIP_TRY(hipGetLastError());
+    std::vector<int32_t> count(L), offset(L);
+    RcdPlan flag_host;
+    HIP_TRY(hipMemcpyAsync(count.data(), class_count, sizeof(int32_t) * L, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipMemcpyAsync(&flag_host, flag, sizeof flag_host, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (flag_host.bad) return RCD_ERR_BAD_LABEL;
+    int32_t run = 0;
+    for (int l = 0; l < L; ++l) {
+        offset[l] = run;
+        run += count[l];
+    }
+    HIP_TRY(hipMemcpyAsync(class_offset, offset.data(), sizeof(int32_t) * L, hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(split::k_scatter, dim3(nchunks), dim3(64), (size_t)L * 4, stream, labels_dev, (long long)N, L,
+                       (const int32_t *)chunk_hist, (const int32_t *)class_offset, idx);
+    HIP_TRY(hipGetLastError());
+
+    // ---- quotas (same r for every class: the extras land on the same workers)
+    std::vector<int64_t> cap((size_t)L * K);
+    for (int l = 0; l < L; ++l) RCD_TRY(rcd_quota(count[l], r_host, K, cap.data() + (size_t)l * K));
+
+    // ---- classes advance in groups that fit the workspace
+    const size_t group_base = cv.off;
+    int l0 = 0;
+    while (l0 < L) {
+        // how many consecutive classes fit?
+        size_t need = 0;
+        int l1 = l0, live = 0;
+        while (l1 < L) {
+            size_t add = 0;
+            int live_next = live;
+            if (count[l1] > 0) {
+                add = class_state_bytes(count[l1], K, true) + up256((size_t)count[l1] * 4);
+                live_next = live + 1;
+            }
+            if (group_base + group_fixed_bytes(std::max(live_next, 1), K) + need + add > workspace_bytes) break;
+            need += add;
+            live = live_next;
+            ++l1;
+        }
+        if (l1 == l0) return RCD_ERR_WORKSPACE;   // not even one class fits
+        if (live > 0) {
+            Carver gc((char *)workspace_dev + group_base, workspace_bytes - group_base);
+            Group g;
+            if (!carve_group_fixed(gc, g, live, K)) return RCD_ERR_WORKSPACE;
+            g.host.resize(live);
+            std::vector<int> cls_of(live);
+            int gi = 0;
+            HIP_TRY(hipMemsetAsync(g.plan_dev, 0, sizeof(RcdPlan), stream));
+            for (int l = l0; l < l1; ++l) {
+                if (count[l] == 0) continue;
+                RcdClass &c = g.host[gi];
+                if (!carve_class(gc, c, count[l], K, cap.data() + (size_t)l * K, true)) return RCD_ERR_WORKSPACE;
+                float *sq = gc.take<float>((size_t)count[l]);
+                if (gc.fail) return RCD_ERR_WORKSPACE;
+                c.assign_out = assign_dev;
+                c.order_out = order_dev;
+                c.out_index = idx + offset[l];
+                RCD_TRY(launch_similarity(X_dev, dt, count[l], d, ld_x, idx + offset[l], sigma2, c.M, c.ld, c.ld, sq,
+                                          stream));
+                cls_of[gi++] = l;
+            }
+            RCD_TRY(run_group(g, stream));
+            std::vector<double> obj((size_t)live * K);
+            HIP_TRY(hipMemcpy(obj.data(), g.obj_dev, sizeof(double) * obj.size(), hipMemcpyDeviceToHost));
+            for (int i = 0; i < live; ++i)
+                memcpy(obj_host + (size_t)cls_of[i] * K, obj.data() + (size_t)i * K, sizeof(double) * K);
+        }
+        l0 = l1;
+    }
+    HIP_TRY(hipStreamSynchronize(stream));
+    return RCD_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,56 @@
+// Device-resident state of the class greedy (Algorithm 1, inner loop) shared by
+// the host orchestration and the kernels.  One RcdClass per class that is being
+// advanced; all classes of a group move in lock step, one "round" at a time:
+//   steps kernel   - runs as many greedy steps as the finished gain rows allow
+//   sweep kernel   - recomputes the gain rows that went stale, for all classes
+//   finalize kernel- adds the row-chunk partial sums in a fixed order
+#pragma once
+#include <stdint.h>
+
+#define RCD_KMAX 16          // must equal RCD_MAX_K of the public header
+#define RCD_TILE 256         // candidate columns per sweep tile (64 lanes x 4)
+#define RCD_CMAX 32          // most row chunks a class's sweep is split into
+#define RCD_SWEEP_THREADS 256
+#define RCD_STEP_THREADS 1024
+
+struct RcdClass {
+    // ---- fixed for the run
+    float *M;            // n x ld working similarity; column p holds S(., perm[p])
+    float *cur;          // K x ld coverage vectors cur_k(j) = max_{a in A_k} S(j,a)
+    float *part;         // RCD_CMAX x K x ld partial gain sums per row chunk
+    float *gain;         // K x ld finished gains, indexed by column position
+    int32_t *perm;       // ld: original (class-local) index held by column p
+    int32_t *assign_out; // caller's arrays (global indexing through out_index)
+    int32_t *order_out;  // nullable
+    const int32_t *out_index; // nullable: position of local sample v in the caller's arrays
+    const void *X;       // recompute mode: features (rows picked through x_index)
+    const int32_t *x_index; // nullable
+    int32_t n, ld, K, total;    // total = sum of quotas
+    int32_t d, ldx, dt, mode;
+    float exp_scale;     // -log2(e) / (2 sigma^2)
+    int32_t target_items;       // sweep workgroups this class should be split into
+    // ---- evolving
+    int32_t nR;          // unassigned samples = live columns
+    int32_t t;           // steps taken
+    int32_t done;
+    int32_t nneed;       // blocks whose gains the next sweep must produce
+    int32_t C, rpc;      // row chunks of the next sweep, rows per chunk
+    int32_t need[RCD_KMAX];
+    int32_t cnt[RCD_KMAX];
+    int32_t cap[RCD_KMAX];
+    int32_t valid[RCD_KMAX];
+    double f[RCD_KMAX];  // running f(A_k): sum of accepted gains
+    // ---- counters
+    int64_t stat_steps, stat_sweeps, stat_entries, stat_useful, stat_computed;
+};
+
+struct RcdPlan {
+    int32_t ncls;
+    int32_t arrive;      // arrival counter of the steps kernel's workgroups
+    int32_t items;       // sweep workgroups with work this round
+    int32_t tiles;       // finalize workgroups with work this round
+    int32_t ndone;       // classes finished
+    int32_t bad;         // set by validation kernels (bad label / similarity out of range)
+    int32_t pad[2];
+    // followed in memory by: int32 item_prefix[ncls+1]; int32 tile_prefix[ncls+1]
+};

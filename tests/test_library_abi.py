@@ -1,0 +1,125 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol that
+include/rcd.h declares, and its host logic (quota rule, workspace sizes,
+argument validation that happens before any launch) behaves."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2211_00839_amd as rcd
+from paper_2211_00839_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.lib_path()):
+        from paper_2211_00839_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "rcd.h")).read()
+    declared = set(re.findall(r"\b(rcd_[a-z_0-9]+)\s*\(", header))
+    assert declared >= {"rcd_similarity", "rcd_partition_class", "rcd_partition_dataset", "rcd_gain_sweep",
+                        "rcd_quota", "rcd_strerror"}
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert set(binding.EXPORTS) == declared
+
+
+def test_strerror_covers_every_status(lib):
+    header = open(os.path.join(ROOT, "include", "rcd.h")).read()
+    codes = [int(v) for v in re.findall(r"RCD_(?:OK|ERR_[A-Z_]+)\s*=\s*(\d+)", header)]
+    assert codes == list(range(len(codes)))
+    texts = [rcd.strerror(c) for c in codes]
+    assert len(set(texts)) == len(texts) and "unknown" not in " ".join(texts)
+    assert rcd.strerror(99) == "unknown status"
+
+
+def test_quota_matches_hand_worked_vectors_and_oracle(lib, golden_dir):
+    with open(os.path.join(golden_dir, "quota_vectors.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            n, r, cap = line.split(";")
+            got = rcd.quota(int(n), [int(x) for x in r.split()])
+            assert got.tolist() == [int(x) for x in cap.split()]
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        K = int(rng.integers(1, 17))
+        r = rng.integers(1, 9, size=K)
+        n = int(rng.integers(0, 100000))
+        assert rcd.quota(n, r).tolist() == oracle.quota(n, r).tolist()
+
+
+def test_quota_rejects_bad_capacities(lib):
+    with pytest.raises(rcd.RcdError) as e:
+        rcd.quota(10, [1, 0])
+    assert e.value.status == 3
+
+
+def test_workspace_sizes_are_aligned_and_monotone(lib):
+    prev = 0
+    for n in (1, 100, 256, 257, 5000):
+        b = rcd.class_workspace_bytes(n, 8, rcd.MODE_STORED)
+        assert b % 256 == 0 and b > prev
+        assert b >= n * n * 4
+        prev = b
+    mn, full = rcd.dataset_workspace_bytes(50000, 10, 5000, 4, rcd.MODE_STORED)
+    assert mn % 256 == 0 and full % 256 == 0 and full >= mn
+    assert full >= 10 * 5000 * 5000 * 4
+
+
+def test_argument_validation_happens_before_any_gpu_work(lib):
+    # none of these reach a launch: they must come back with a status, not crash
+    cap = np.array([1, 1], dtype=np.int64)
+    obj = np.zeros(2)
+    vp = ctypes.c_void_p
+    call = lib.rcd_partition_class
+    # K too large -> unsupported
+    big = np.ones(17, dtype=np.int64)
+    assert call(None, 0, None, 0, 0, 0, 1.0, 10, 17, big.ctypes.data_as(vp), None, None,
+                np.zeros(17).ctypes.data_as(vp), None, 0, None) == 4
+    # negative quota / quotas above n -> bad capacity
+    neg = np.array([-1, 2], dtype=np.int64)
+    assert call(None, 0, None, 0, 0, 0, 1.0, 10, 2, neg.ctypes.data_as(vp), None, None, obj.ctypes.data_as(vp),
+                None, 0, None) == 3
+    over = np.array([6, 6], dtype=np.int64)
+    assert call(None, 0, None, 0, 0, 0, 1.0, 10, 2, over.ctypes.data_as(vp), None, None, obj.ctypes.data_as(vp),
+                None, 0, None) == 3
+    # n < 0, K < 1 -> invalid argument
+    assert call(None, 0, None, 0, 0, 0, 1.0, -1, 2, cap.ctypes.data_as(vp), None, None, obj.ctypes.data_as(vp),
+                None, 0, None) == 1
+    assert call(None, 0, None, 0, 0, 0, 1.0, 10, 0, cap.ctypes.data_as(vp), None, None, obj.ctypes.data_as(vp),
+                None, 0, None) == 1
+    # empty class is legal and touches nothing
+    zero = np.array([0, 0], dtype=np.int64)
+    assert call(None, 0, None, 0, 0, 0, 1.0, 0, 2, zero.ctypes.data_as(vp), None, None, obj.ctypes.data_as(vp),
+                None, 0, None) == 0
+    # similarity: bad dtype, bad sigma
+    sim = lib.rcd_similarity
+    assert sim(None, 7, 4, 4, 4, None, 1.0, None, 4, None, 0, None) == 4
+    assert sim(None, 0, 4, 4, 4, None, 0.0, None, 4, None, 0, None) == 1
+    assert sim(None, 0, 4, 4, 2, None, 1.0, None, 4, None, 0, None) == 1
+    # data set: capacity < 1, bad mode
+    r = np.array([1, 0], dtype=np.int32)
+    ds = lib.rcd_partition_dataset
+    assert ds(None, 0, 10, 4, 4, None, 2, r.ctypes.data_as(vp), 2, 1.0, 0, None, None,
+              np.zeros(4).ctypes.data_as(vp), None, 0, None) == 3
+    r = np.array([1, 1], dtype=np.int32)
+    assert ds(None, 0, 10, 4, 4, None, 2, r.ctypes.data_as(vp), 2, 1.0, 9, None, None,
+              np.zeros(4).ctypes.data_as(vp), None, 0, None) == 4
+
+
+def test_python_binding_refuses_cpu_tensors(lib):
+    import torch
+
+    with pytest.raises(rcd.RcdError):
+        rcd.similarity(torch.zeros(4, 4), 1.0, workspace=torch.zeros(256, dtype=torch.uint8))
