@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the partitioner's hot path on one MI355X.
+
+One "step" = one full pass of the path over one synthetic data set already
+resident in HBM: class split, quotas, similarity build of every class, and the
+Algorithm-1 greedy of every class (gain sweeps, argmax, coverage updates),
+through the C ABI entry point rcd_partition_dataset.
+
+Prints ONE JSON line.  `value` = gain evaluations Algorithm 1 consumes per
+second (sum over steps of the number of unassigned candidates, over the whole
+job's wall time, similarity build included).  `roofline` covers the gain-sweep
+kernel: algorithmic bytes (4 B per similarity entry of a live candidate column,
+counted by the kernels themselves) over the kernel's time between HIP events
+recorded around each of its launches in an extra, instrumented pass of the same
+step.  `cpu_baseline` times the CPU oracle on a bounded sample on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def describe(w, ds):
+    return (f"{w.name}: {ds.L} classes x {w.n_c} samples, d={ds.X.shape[1]} {w.dtype}, K={len(ds.r)} "
+            f"capacities {ds.r.tolist()}, Gaussian-mixture features, RBF sigma^2=d, seed {w.seed}")
+
+
+def cpu_baseline(ds, budget_steps):
+    """Oracle as it stands, one thread, on class 0 of the workload: its similarity
+    matrix in full, then the first `budget_steps` greedy steps on it."""
+    import oracle
+
+    idx = np.flatnonzero(ds.labels == 0)
+    n = len(idx)
+    t0 = time.perf_counter()
+    S0 = oracle.similarity(ds.X[idx], ds.sigma2)
+    t_sim = time.perf_counter() - t0
+    cap = oracle.quota(n, ds.r)
+    # same proportions, cut to the window: the per-step work (|R_t| x n terms) is the real one
+    win = np.floor(cap * (budget_steps / n)).astype(np.int64)
+    win[-1] += budget_steps - win.sum()
+    t0 = time.perf_counter()
+    out = oracle.partition_class(S0, win)
+    t_greedy = time.perf_counter() - t0
+    steps = out["steps"]
+    evals = sum(n - t for t in range(steps))
+    # whole-job estimate: every class pays its similarity build and n(n+1)/2 gain evaluations
+    job_evals = ds.L * n * (n + 1) / 2
+    job_time = ds.L * t_sim + job_evals / (evals / t_greedy)
+    return {
+        "value": job_evals / job_time,
+        "unit": "gain-evals/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": (f"class 0 of the workload (n={n}): its full oracle similarity matrix ({t_sim:.2f} s) and the "
+                   f"first {steps} greedy steps on it ({t_greedy:.2f} s, {evals / t_greedy:.4g} gain-evals/s in "
+                   f"the window); value = whole-job rate extrapolated from both"),
+        "greedy_window_evals_per_s": evals / t_greedy,
+        "similarity_s_per_class": t_sim,
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cifar10")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scale", default="", help="L,n_c,d override for quick runs (not a valid bench line)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2211_00839_amd as rcd
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: there is no CPU path", file=sys.stderr)
+        sys.exit(2)
+    rcd.load_library()
+    torch.cuda.set_device(0)
+
+    w = si.WORKLOADS[args.workload]
+    kw = {}
+    if args.scale:
+        L, n_c, d = (int(x) for x in args.scale.split(","))
+        kw = dict(L=L, n_c=n_c, d=d)
+    ds = si.make_dataset(w, **kw)
+    N, d = ds.X.shape
+    K = len(ds.r)
+    if ds.X.dtype == np.uint16:
+        X = torch.from_numpy(ds.X.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        X = torch.from_numpy(ds.X).cuda()
+    labels = torch.from_numpy(ds.labels).cuda()
+    counts = np.bincount(ds.labels, minlength=ds.L)
+    _, full = rcd.dataset_workspace_bytes(N, ds.L, int(counts.max()), K, rcd.MODE_STORED)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+
+    def step():
+        return rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, rcd.MODE_STORED, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        assign, order, obj = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stats = rcd.last_stats()
+    ms_per_step = 1e3 * elapsed / max(args.steps, 1)
+    value = stats["useful_evals"] / (ms_per_step * 1e-3)
+
+    # instrumented pass of the same step: HIP events around every launch of a round
+    rcd.profile(True)
+    t1 = time.perf_counter()
+    step()
+    torch.cuda.synchronize()
+    prof_ms = 1e3 * (time.perf_counter() - t1)
+    prof = rcd.profile_read()
+    pstats = rcd.last_stats()
+    rcd.profile(False)
+    sweep_bytes = 4.0 * pstats["entries_streamed"]
+    achieved = sweep_bytes / (prof["sweep_ms"] * 1e-3) / 1e9 if prof["sweep_ms"] > 0 else 0.0
+    roofline = {
+        "kernel": "rcd_k_sweep",
+        "bound": "hbm",
+        "achieved": achieved,
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS,
+        "traffic": None,
+        "launches": prof["rounds"],
+        "avg_launch_us": 1e3 * prof["sweep_ms"] / max(prof["rounds"], 1),
+        "bytes_per_launch": sweep_bytes / max(prof["rounds"], 1),
+        "sweeps_with_work": pstats["sweeps"],
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "sweep_traffic.json")
+    if os.path.exists(traffic_file) and not args.scale and args.workload == "cifar10":
+        with open(traffic_file) as fh:
+            roofline["traffic"] = json.load(fh).get("hbm_bytes_per_launch")
+
+    out = {
+        "metric": "marginal-gain evals/sec (gain evaluations Algorithm 1 consumes / whole-job wall time)",
+        "value": value,
+        "unit": "gain-evals/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if ds.X.dtype == np.float32 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": describe(w, ds), "mode": "stored S, all classes advanced together",
+                   "scaled_down": bool(args.scale)},
+        "partition_wall_time_s": ms_per_step * 1e-3,
+        "useful_evals_per_step": stats["useful_evals"],
+        "computed_evals_per_step": stats["computed_evals"],
+        "greedy_steps": stats["steps"],
+        "sweeps": stats["sweeps"],
+        "kernel_launches": stats["launches"],
+        "time_split_ms": {"similarity": prof["similarity_ms"], "steps": prof["steps_ms"], "sweep": prof["sweep_ms"],
+                          "finalize": prof["finalize_ms"], "instrumented_step_total": prof_ms},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        n0 = int(counts[0])
+        out["cpu_baseline"] = cpu_baseline(ds, budget_steps=min(96, n0))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

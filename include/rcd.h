@@ -149,6 +149,18 @@ const char *rcd_last_hip_error(void);
  */
 void rcd_last_stats(int64_t *out6_host);
 
+/*
+ * Per-kernel timing for benchmarks.  rcd_profile(1) makes the calling thread's
+ * later partition calls put HIP events between the launches of every round
+ * (on the caller's stream) and add up the elapsed times; rcd_profile(0) turns
+ * it off; either call clears the sums.  rcd_profile_read: out[0..2] = ms spent
+ * in the steps / gain-sweep / finalize launches, out[3] = rounds timed (each
+ * launches the three kernels once), out[4] = ms of the similarity builds of
+ * rcd_partition_dataset, out[5..7] = 0.
+ */
+void rcd_profile(int enable);
+void rcd_profile_read(double *out8_host);
+
 #ifdef __cplusplus
 }
 #endif

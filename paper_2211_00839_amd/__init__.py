@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     load_library,
     partition_class,
     partition_dataset,
+    profile,
+    profile_read,
     quota,
     similarity,
     strerror,

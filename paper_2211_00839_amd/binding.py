@@ -16,6 +16,7 @@ EXPORTS = [
     "rcd_similarity", "rcd_similarity_workspace_bytes", "rcd_quota", "rcd_gain_sweep",
     "rcd_partition_class", "rcd_partition_dataset", "rcd_class_workspace_bytes",
     "rcd_dataset_workspace_bytes", "rcd_strerror", "rcd_last_hip_error", "rcd_last_stats",
+    "rcd_profile", "rcd_profile_read",
 ]
 
 
@@ -64,6 +65,10 @@ def load_library():
     lib.rcd_last_hip_error.argtypes = []
     lib.rcd_last_stats.restype = None
     lib.rcd_last_stats.argtypes = [vp]
+    lib.rcd_profile.restype = None
+    lib.rcd_profile.argtypes = [i32]
+    lib.rcd_profile_read.restype = None
+    lib.rcd_profile_read.argtypes = [vp]
     _lib = lib
     return lib
 
@@ -222,3 +227,13 @@ def last_stats() -> dict:
     load_library().rcd_last_stats(_np_ptr(out))
     keys = ["steps", "sweeps", "entries_streamed", "useful_evals", "launches", "computed_evals"]
     return dict(zip(keys, (int(v) for v in out)))
+
+
+def profile(enable: bool) -> None:
+    load_library().rcd_profile(1 if enable else 0)
+
+
+def profile_read() -> dict:
+    out = np.zeros(8, dtype=np.float64)
+    load_library().rcd_profile_read(_np_ptr(out))
+    return dict(steps_ms=out[0], sweep_ms=out[1], finalize_ms=out[2], rounds=int(out[3]), similarity_ms=out[4])

@@ -22,6 +22,10 @@ namespace {
 thread_local char g_hip_err[320] = "";
 thread_local int64_t g_stats[6] = {0, 0, 0, 0, 0, 0};
 thread_local RcdPlan *g_pinned = nullptr;   // 2 progress slots, pinned, never freed
+// optional per-kernel timing (HIP events between the launches of a round)
+thread_local int g_profile_on = 0;
+thread_local double g_prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // ms: steps, sweep, finalize; rounds; similarity ms
+thread_local std::vector<hipEvent_t> g_prof_ev[2];
 
 #define HIP_TRY(expr)                                                                      \
     do {                                                                                   \
@@ -171,6 +175,27 @@ int run_group(Group &g, hipStream_t stream)
     const int rounds = env_int("RCD_ROUNDS_PER_BATCH", 16, 1, 1024);
     int64_t launches = 1;
     int rc = RCD_OK;
+    const bool prof = g_profile_on != 0;
+    if (prof) {
+        for (int s = 0; s < 2; ++s)
+            while ((int)g_prof_ev[s].size() < 3 * rounds + 1) {
+                hipEvent_t e;
+                HIP_TRY(hipEventCreate(&e));
+                g_prof_ev[s].push_back(e);
+            }
+    }
+    int64_t prof_done = 0;   // batches whose events have been read
+    int64_t last_batch = -1; // last batch that was enqueued in full
+    auto read_events = [&](int64_t batch) {
+        std::vector<hipEvent_t> &e = g_prof_ev[batch & 1];
+        for (int r = 0; r < rounds; ++r) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, e[3 * r], e[3 * r + 1]) == hipSuccess) g_prof[0] += ms;
+            if (hipEventElapsedTime(&ms, e[3 * r + 1], e[3 * r + 2]) == hipSuccess) g_prof[1] += ms;
+            if (hipEventElapsedTime(&ms, e[3 * r + 2], e[3 * r + 3]) == hipSuccess) g_prof[2] += ms;
+        }
+        g_prof[3] += rounds;
+    };
     // every round takes at least one step in every unfinished class, so this
     // many batches always suffice; running past it means a defect, not work
     int64_t max_total = 0;
@@ -182,13 +207,18 @@ int run_group(Group &g, hipStream_t stream)
             rc = RCD_ERR_HIP;
             break;
         }
+        std::vector<hipEvent_t> *pe = prof ? &g_prof_ev[b & 1] : nullptr;
+        if (pe) (void)hipEventRecord((*pe)[0], stream);
         for (int r = 0; r < rounds; ++r) {
             hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev,
                                g.plan_dev, 0);
+            if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
             hipLaunchKernelGGL(rcd_k_sweep, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream,
                                (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
+            if (pe) (void)hipEventRecord((*pe)[3 * r + 2], stream);
             hipLaunchKernelGGL(rcd_k_finalize, dim3(tiles_ub), dim3(RCD_TILE), 0, stream,
                                (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
+            if (pe) (void)hipEventRecord((*pe)[3 * r + 3], stream);
         }
         launches += 3 * (int64_t)rounds;
         hipError_t le = hipGetLastError();
@@ -212,12 +242,15 @@ int run_group(Group &g, hipStream_t stream)
                 rc = RCD_ERR_HIP;
                 break;
             }
+            if (prof) { read_events(b - 1); prof_done = b; }
             const RcdPlan &seen = g_pinned[(b - 1) & 1];
-            if (seen.bad) { rc = RCD_ERR_BAD_SIMILARITY; break; }
-            if (seen.ndone >= ncls) break;
+            if (seen.bad) { rc = RCD_ERR_BAD_SIMILARITY; last_batch = b; break; }
+            if (seen.ndone >= ncls) { last_batch = b; break; }
         }
     }
     hipError_t es = hipStreamSynchronize(stream);
+    if (prof && es == hipSuccess && rc == RCD_OK)
+        for (int64_t b = prof_done; b <= last_batch; ++b) read_events(b);
     hipEventDestroy(ev[0]);
     hipEventDestroy(ev[1]);
     if (rc != RCD_OK) return rc;
@@ -315,6 +348,17 @@ const char *rcd_last_hip_error(void) { return g_hip_err; }
 void rcd_last_stats(int64_t *out6_host)
 {
     if (out6_host) memcpy(out6_host, g_stats, sizeof g_stats);
+}
+
+void rcd_profile(int enable)
+{
+    g_profile_on = enable ? 1 : 0;
+    memset(g_prof, 0, sizeof g_prof);
+}
+
+void rcd_profile_read(double *out8_host)
+{
+    if (out8_host) memcpy(out8_host, g_prof, sizeof g_prof);
 }
 
 size_t rcd_similarity_workspace_bytes(int64_t n) { return n > 0 ? up256((size_t)n * 4) : 0; }
@@ -560,6 +604,12 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
             std::vector<int> cls_of(live);
             int gi = 0;
             HIP_TRY(hipMemsetAsync(g.plan_dev, 0, sizeof(RcdPlan), stream));
+            hipEvent_t sim_ev[2] = {nullptr, nullptr};
+            if (g_profile_on) {
+                HIP_TRY(hipEventCreate(&sim_ev[0]));
+                HIP_TRY(hipEventCreate(&sim_ev[1]));
+                HIP_TRY(hipEventRecord(sim_ev[0], stream));
+            }
             for (int l = l0; l < l1; ++l) {
                 if (count[l] == 0) continue;
                 RcdClass &c = g.host[gi];
@@ -573,7 +623,14 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
                                           stream));
                 cls_of[gi++] = l;
             }
+            if (g_profile_on) HIP_TRY(hipEventRecord(sim_ev[1], stream));
             RCD_TRY(run_group(g, stream));
+            if (g_profile_on) {
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, sim_ev[0], sim_ev[1]) == hipSuccess) g_prof[4] += ms;
+                (void)hipEventDestroy(sim_ev[0]);
+                (void)hipEventDestroy(sim_ev[1]);
+            }
             std::vector<double> obj((size_t)live * K);
             HIP_TRY(hipMemcpy(obj.data(), g.obj_dev, sizeof(double) * obj.size(), hipMemcpyDeviceToHost));
             for (int i = 0; i < live; ++i)
