@@ -146,17 +146,18 @@ const char *rcd_last_hip_error(void);
  *          (gain evaluations Algorithm 1 consumes)
  *   out[4] kernel launches           out[5] sum over sweeps of blocks evaluated
  *          x candidates (gain evaluations computed)
+ *   out[6] 10 ns ticks spent in the step loops, summed over classes   out[7] 0
  */
-void rcd_last_stats(int64_t *out6_host);
+void rcd_last_stats(int64_t *out8_host);
 
 /*
  * Per-kernel timing for benchmarks.  rcd_profile(1) makes the calling thread's
  * later partition calls put HIP events between the launches of every round
  * (on the caller's stream) and add up the elapsed times; rcd_profile(0) turns
- * it off; either call clears the sums.  rcd_profile_read: out[0..2] = ms spent
- * in the steps / gain-sweep / finalize launches, out[3] = rounds timed (each
- * launches the three kernels once), out[4] = ms of the similarity builds of
- * rcd_partition_dataset, out[5..7] = 0.
+ * it off; either call clears the sums.  rcd_profile_read: out[0] = ms spent in
+ * the steps launches, out[1] = ms in the gain-sweep launches, out[2] = 0,
+ * out[3] = rounds timed (each launches the two kernels once), out[4] = ms of
+ * the similarity builds of rcd_partition_dataset, out[5..7] = 0.
  */
 void rcd_profile(int enable);
 void rcd_profile_read(double *out8_host);

@@ -223,9 +223,9 @@ def partition_dataset(X, labels, L: int, r, sigma2: float, mode: int = 0, worksp
 
 
 def last_stats() -> dict:
-    out = np.zeros(6, dtype=np.int64)
+    out = np.zeros(8, dtype=np.int64)
     load_library().rcd_last_stats(_np_ptr(out))
-    keys = ["steps", "sweeps", "entries_streamed", "useful_evals", "launches", "computed_evals"]
+    keys = ["steps", "sweeps", "entries_streamed", "useful_evals", "launches", "computed_evals", "step_ticks"]
     return dict(zip(keys, (int(v) for v in out)))
 
 
@@ -236,4 +236,4 @@ def profile(enable: bool) -> None:
 def profile_read() -> dict:
     out = np.zeros(8, dtype=np.float64)
     load_library().rcd_profile_read(_np_ptr(out))
-    return dict(steps_ms=out[0], sweep_ms=out[1], finalize_ms=out[2], rounds=int(out[3]), similarity_ms=out[4])
+    return dict(steps_ms=out[0], sweep_ms=out[1], rounds=int(out[3]), similarity_ms=out[4])

@@ -27,6 +27,42 @@ typedef f32x4 RCD_GLOBAL *gf32x4;
 // constant address space, which lets wave-uniform reads use the scalar unit.
 typedef const float __attribute__((address_space(4))) *ccf32;
 
+// Data handed from one workgroup to another inside a launch (sweep partials,
+// finished gains, a class's published state) is written and read at device
+// scope: such stores go through to memory and such loads do not hit another
+// XCD's stale L2 lines, so no cache-wide write-back or invalidate is needed.
+// The hand-over itself is "wait for my stores, barrier, bump a counter".
+__device__ __forceinline__ void dev_store(float RCD_GLOBAL *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void dev_store(int32_t RCD_GLOBAL *p, int32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float dev_load(const float RCD_GLOBAL *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t dev_load(const int32_t RCD_GLOBAL *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_for_my_stores()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+// true in exactly one workgroup: the one whose arrival completes `expected`
+__device__ __forceinline__ bool arrive_last(int32_t *counter, int expected, int *s_flag)
+{
+    wait_for_my_stores();
+    __syncthreads();
+    if (threadIdx.x == 0)
+        *s_flag = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1);
+    __syncthreads();
+    return *s_flag != 0;
+}
+
 __device__ __forceinline__ float clamp01(float x)
 {
     // S in [0,1] and cur in [0,1] give S-cur in [-1,1]: max(0, S-cur) is the
@@ -34,17 +70,18 @@ __device__ __forceinline__ float clamp01(float x)
     return __builtin_amdgcn_fmed3f(x, 0.0f, 1.0f);
 }
 
-__device__ __forceinline__ const int32_t *item_prefix(const RcdPlan *plan)
+// two plan headers, then two prefix arrays of ncls+1 entries
+__device__ __forceinline__ int32_t *plan_prefix(RcdPlan *plans, int buf)
 {
-    return reinterpret_cast<const int32_t *>(plan + 1);
+    return reinterpret_cast<int32_t *>(plans + 2) + (size_t)buf * (plans[0].ncls + 1);
 }
-__device__ __forceinline__ const int32_t *tile_prefix(const RcdPlan *plan)
+__device__ __forceinline__ const int32_t *plan_prefix(const RcdPlan *plans, int buf)
 {
-    return reinterpret_cast<const int32_t *>(plan + 1) + (plan->ncls + 1);
+    return reinterpret_cast<const int32_t *>(plans + 2) + (size_t)buf * (plans[0].ncls + 1);
 }
 
 // largest c with prefix[c] <= item (prefix is non-decreasing, prefix[ncls] > item)
-__device__ __forceinline__ int find_class(const int32_t *__restrict__ prefix, int ncls, int item)
+__device__ __forceinline__ int find_class(const int32_t *prefix, int ncls, int item)
 {
     int lo = 0, hi = ncls;
     while (hi - lo > 1) {
@@ -57,7 +94,7 @@ __device__ __forceinline__ int find_class(const int32_t *__restrict__ prefix, in
 // ---------------------------------------------------------------------------
 // Gain sweep (GreedyStep's objective for every candidate and every stale block):
 //   part[chunk][k][p] = sum_{j in chunk} max(0, M[j][p] - cur_k(j))
-// One workgroup = 4 waves on one 256-column tile; wave w takes the w-th quarter
+// One workgroup = 8 waves on one 256-column tile; wave w takes the w-th eighth
 // of the chunk's rows.  KS = number of blocks evaluated (compile-time so the
 // accumulators stay in registers).
 // ---------------------------------------------------------------------------
@@ -69,7 +106,7 @@ __device__ __forceinline__ void sweep_body(const RcdClass &st, int tile, int chu
     // counters and coverage addresses live in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ld = st.ld;
-    const int rpw = st.rpc >> 2;
+    const int rpw = st.rpc / RCD_SWEEP_WAVES;
     const int row0 = chunk * st.rpc + wave * rpw;
     const int row1 = min(st.n, row0 + rpw);
     const int nneed = st.nneed;
@@ -115,8 +152,8 @@ __device__ __forceinline__ void sweep_body(const RcdClass &st, int tile, int chu
         }
     }
 
-    // Add the four waves' sums in wave order, four blocks at a time.
-    // lds is [wave 4][block-in-group 4][lane 64] float4 = 16 KB.
+    // Add the waves' sums in wave order, four blocks at a time.
+    // lds is [wave][block-in-group 4][lane 64] float4.
     const gf32 part = (gf32)st.part + (size_t)chunk * st.K * ld + (size_t)tile * RCD_TILE + lane * 4;
 #pragma unroll
     for (int g0 = 0; g0 < KS; g0 += 4) {
@@ -125,77 +162,28 @@ __device__ __forceinline__ void sweep_body(const RcdClass &st, int tile, int chu
             if (g0 + i < KS) lds[(wave * 4 + i) * 64 + lane] = acc[g0 + i];
         __syncthreads();
         const int mine = g0 + wave;
-        if (mine < KS && mine < nneed) {
+        if (wave < 4 && mine < KS && mine < nneed) {
             float4 a = lds[(0 * 4 + wave) * 64 + lane];
-            const float4 b = lds[(1 * 4 + wave) * 64 + lane];
-            const float4 c = lds[(2 * 4 + wave) * 64 + lane];
-            const float4 e = lds[(3 * 4 + wave) * 64 + lane];
-            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-            a.x += c.x; a.y += c.y; a.z += c.z; a.w += c.w;
-            a.x += e.x; a.y += e.y; a.z += e.z; a.w += e.w;
+#pragma unroll
+            for (int w = 1; w < RCD_SWEEP_WAVES; ++w) {
+                const float4 b = lds[(w * 4 + wave) * 64 + lane];
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
             int kmine = kb[0];
 #pragma unroll
             for (int i = 0; i < KS; ++i)
                 if (i == mine) kmine = kb[i];
-            f32x4 out;
-            out.x = a.x; out.y = a.y; out.z = a.z; out.w = a.w;
-            *(gf32x4)(part + (size_t)kmine * ld) = out;
+            const gf32 dst = part + (size_t)kmine * ld;
+            dev_store(dst + 0, a.x); dev_store(dst + 1, a.y);
+            dev_store(dst + 2, a.z); dev_store(dst + 3, a.w);
         }
         __syncthreads();
     }
 }
 
-} // namespace
-
-extern "C" __global__ void __launch_bounds__(RCD_SWEEP_THREADS)
-rcd_k_sweep(const RcdClass *__restrict__ classes, const RcdPlan *__restrict__ plan)
-{
-    __shared__ float4 lds[4 * 4 * 64];
-    const int item = blockIdx.x;
-    if (item >= plan->items) return;
-    const int ncls = plan->ncls;
-    const int32_t *__restrict__ prefix = item_prefix(plan);
-    const int c = ncls > 1 ? find_class(prefix, ncls, item) : 0;
-    const RcdClass &st = classes[c];
-    const int local = item - prefix[c];
-    const int tiles = (st.nR + RCD_TILE - 1) / RCD_TILE;
-    const int tile = local % tiles;
-    const int chunk = local / tiles;
-    const int nneed = st.nneed;
-    if (nneed <= 1) sweep_body<1>(st, tile, chunk, lds);
-    else if (nneed == 2) sweep_body<2>(st, tile, chunk, lds);
-    else if (nneed == 3) sweep_body<3>(st, tile, chunk, lds);
-    else if (nneed == 4) sweep_body<4>(st, tile, chunk, lds);
-    else if (nneed <= 6) sweep_body<6>(st, tile, chunk, lds);
-    else if (nneed <= 8) sweep_body<8>(st, tile, chunk, lds);
-    else if (nneed <= 12) sweep_body<12>(st, tile, chunk, lds);
-    else sweep_body<16>(st, tile, chunk, lds);
-}
-
-// gain[k][p] = sum over row chunks, in chunk order, of part[chunk][k][p].
-extern "C" __global__ void __launch_bounds__(RCD_TILE)
-rcd_k_finalize(const RcdClass *__restrict__ classes, const RcdPlan *__restrict__ plan)
-{
-    const int item = blockIdx.x;
-    if (item >= plan->tiles) return;
-    const int ncls = plan->ncls;
-    const int32_t *__restrict__ prefix = tile_prefix(plan);
-    const int c = ncls > 1 ? find_class(prefix, ncls, item) : 0;
-    const RcdClass &st = classes[c];
-    const int tile = item - prefix[c];
-    const int col = tile * RCD_TILE + threadIdx.x;
-    const int ld = st.ld, K = st.K, C = st.C;
-    for (int i = 0; i < st.nneed; ++i) {
-        const int k = st.need[i];
-        const float *__restrict__ p = st.part + (size_t)k * ld + col;
-        float g = 0.f;
-        for (int ch = 0; ch < C; ++ch) g += p[(size_t)ch * K * ld];
-        st.gain[(size_t)k * ld + col] = g;
-    }
-}
-
 // ---------------------------------------------------------------------------
-// Steps kernel: one workgroup per class.  Repeats Algorithm 1's loop body
+// Greedy steps of one class, run by one workgroup of NT threads.  Repeats
+// Algorithm 1's loop body
 //   j* = argmin over non-full blocks of f (lowest index on ties)
 //   v* = argmax over unassigned v of the gain for block j* (lowest index on ties)
 //   A_j* += v*, R -= v*, coverage update cur_j*(j) = max(cur_j*(j), S(j, v*))
@@ -210,175 +198,365 @@ __device__ __forceinline__ unsigned long long pack_key(float g, int v)
     return ((unsigned long long)__float_as_uint(g) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)v);
 }
 
-extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
-rcd_k_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plan, int target_total)
-{
-    __shared__ double s_f[RCD_KMAX];
-    __shared__ int s_cnt[RCD_KMAX], s_cap[RCD_KMAX], s_valid[RCD_KMAX];
-    __shared__ unsigned long long s_wkey[RCD_STEP_THREADS / 64];
-    __shared__ int s_wpos[RCD_STEP_THREADS / 64];
-    __shared__ int s_last_arrival;
+typedef const int32_t RCD_GLOBAL *gci32;
+typedef int32_t RCD_GLOBAL *gi32;
 
-    RcdClass &st = classes[blockIdx.x];
+struct StepShared {
+    double f[RCD_KMAX];
+    int cnt[RCD_KMAX], cap[RCD_KMAX], valid[RCD_KMAX];
+    unsigned long long wkey[RCD_STEP_THREADS / 64];
+    int wpos[RCD_STEP_THREADS / 64];
+    // columns displaced during this call: live position ppos[i] now shows the
+    // column that was at position psrc[i] when the call began
+    int npatch, ppos[RCD_KMAX], psrc[RCD_KMAX];
+    // the steps taken: block, column (position at the start of the call) that
+    // was taken, sample, step index, gain
+    int nupd, ujs[RCD_KMAX], usrc[RCD_KMAX], uv[RCD_KMAX], ut[RCD_KMAX];
+};
+
+// position at the start of the call of the column now shown at position p
+__device__ __forceinline__ int effective_pos(const StepShared &sh, int npatch, int p)
+{
+    int e = p;
+    for (int i = 0; i < npatch; ++i)
+        if (sh.ppos[i] == p) e = sh.psrc[i];
+    return e;
+}
+
+// Only the decisions are taken here, so that one step costs one trip to memory:
+// argmin block, argmax column (gains and perm are read through the list of
+// columns displaced so far, nothing of the matrix is touched), bookkeeping in
+// LDS.  The consequences - coverage updates from the taken columns, moving the
+// displaced columns, their gains and perm entries, the caller's output arrays -
+// are applied by rcd_k_apply, which has the whole GPU for the strided column
+// traffic.  A block is stepped at most once per call (its gains go stale), so
+// a call takes at most K steps.
+template <int NT>
+__device__ __forceinline__ void class_steps(RcdClass &st, StepShared &sh)
+{
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     int done = st.done;
+    if (done) {
+        if (tid == 0) dev_store((gi32)&st.nneed, 0);
+        return;
+    }
+    const int K = st.K, n = st.n, ld = st.ld, total = st.total;
+    const long long tick0 = wall_clock64();
+    __syncthreads();
+    if (tid < RCD_KMAX) {
+        sh.f[tid] = st.f[tid];
+        sh.cnt[tid] = st.cnt[tid];
+        sh.cap[tid] = st.cap[tid];
+        sh.valid[tid] = st.valid[tid];
+    }
+    if (tid == 0) { sh.npatch = 0; sh.nupd = 0; }
+    __syncthreads();
+    // the sweep that ran since the last call rebuilt these rows
+    if (tid < st.nneed) sh.valid[st.need[tid]] = 1;
+    __syncthreads();
 
-    if (!done) {
-        const int K = st.K, n = st.n, ld = st.ld, total = st.total;
-        if (tid < RCD_KMAX) {
-            s_f[tid] = st.f[tid];
-            s_cnt[tid] = st.cnt[tid];
-            s_cap[tid] = st.cap[tid];
-            s_valid[tid] = st.valid[tid];
+    const int nR0 = st.nR, t0 = st.t;
+    int nR = nR0, t = t0;
+    long long useful = 0;
+    const gf32 M = (gf32)st.M;
+    const gf32 gain = (gf32)st.gain;
+    const gi32 perm = (gi32)st.perm;
+
+    // ---- A. decide
+    for (;;) {
+        if (t >= total) { done = 1; break; }
+        int js = -1;
+        double fbest = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (sh.cnt[k] >= sh.cap[k]) continue;
+            const double fk = sh.f[k];
+            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
         }
-        __syncthreads();
-        // the sweep + finalize that ran since the last call rebuilt these rows
-        if (tid < st.nneed) s_valid[st.need[tid]] = 1;
-        __syncthreads();
+        if (js < 0) { done = 1; break; }
+        if (!sh.valid[js]) break;
 
-        int nR = st.nR, t = st.t;
-        long long useful = 0;
-        float *const M = st.M;
-        int32_t *const perm = st.perm;
-
-        for (;;) {
-            if (t >= total) { done = 1; break; }
-            int js = -1;
-            double fbest = 0.0;
-            for (int k = 0; k < K; ++k) {
-                if (s_cnt[k] >= s_cap[k]) continue;
-                const double fk = s_f[k];
-                if (js < 0 || fk < fbest) { js = k; fbest = fk; }
-            }
-            if (js < 0) { done = 1; break; }
-            if (!s_valid[js]) break;
-
-            // masked argmax over the live columns
-            const float *g = st.gain + (size_t)js * ld;
-            unsigned long long best = 0ull;
-            int bpos = -1;
-            for (int p = tid; p < nR; p += RCD_STEP_THREADS) {
-                const unsigned long long key = pack_key(g[p], perm[p]);
-                if (key > best) { best = key; bpos = p; }
+        const gcf32 g = (gcf32)gain + (size_t)js * ld;
+        const int npatch = sh.npatch;
+        unsigned long long best = 0ull;
+        int bpos = -1;
+        for (int p0 = 0; p0 < nR; p0 += 8 * NT) {
+            float gv[8];
+            int pv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * NT + tid;
+                if (p < nR) {
+                    const int e = npatch ? effective_pos(sh, npatch, p) : p;
+                    gv[u] = dev_load(g + e);
+                    pv[u] = perm[e];
+                }
             }
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const unsigned long long ok = __shfl_xor(best, off);
-                const int op = __shfl_xor(bpos, off);
-                if (ok > best) { best = ok; bpos = op; }
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * NT + tid;
+                if (p < nR) {
+                    const unsigned long long key = pack_key(gv[u], pv[u]);
+                    if (key > best) { best = key; bpos = p; }
+                }
             }
-            if (lane == 0) { s_wkey[wave] = best; s_wpos[wave] = bpos; }
-            __syncthreads();
-            best = s_wkey[0]; bpos = s_wpos[0];
-#pragma unroll
-            for (int w = 1; w < RCD_STEP_THREADS / 64; ++w) {
-                const unsigned long long ok = s_wkey[w];
-                if (ok > best) { best = ok; bpos = s_wpos[w]; }
-            }
-            const float gbest = __uint_as_float((unsigned)(best >> 32));
-            const int vstar = (int)(0xFFFFFFFFu - (unsigned)(best & 0xFFFFFFFFull));
-            const int pstar = bpos;
-            const int last = nR - 1;
-
-            // coverage update from column p*, then compaction: last live column -> p*
-            float *cur = st.cur + (size_t)js * ld;
-            for (int j = tid; j < n; j += RCD_STEP_THREADS) {
-                float *row = M + (size_t)j * ld;
-                const float s = row[pstar];
-                if (s > cur[j]) cur[j] = s;
-                if (pstar != last) row[pstar] = row[last];
-            }
-            if (pstar != last) {
-                if (tid < K) st.gain[(size_t)tid * ld + pstar] = st.gain[(size_t)tid * ld + last];
-                if (tid == 64) perm[pstar] = perm[last];
-            }
-            if (tid == 0) {
-                const int oi = st.out_index ? st.out_index[vstar] : vstar;
-                st.assign_out[oi] = js;
-                if (st.order_out) st.order_out[oi] = t;
-            }
-            __syncthreads();   // everyone has read s_f/s_cnt/s_valid/s_wkey of this step
-            if (tid == 0) {
-                s_cnt[js] += 1;
-                s_f[js] += (double)gbest;
-                s_valid[js] = 0;
-            }
-            useful += nR;
-            nR = last;
-            ++t;
-            __syncthreads();
         }
-
-        // publish the state and what the next sweep must do
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const unsigned long long ok = __shfl_xor(best, off);
+            const int op = __shfl_xor(bpos, off);
+            if (ok > best) { best = ok; bpos = op; }
+        }
+        if (lane == 0) { sh.wkey[wave] = best; sh.wpos[wave] = bpos; }
+        __syncthreads();
+        best = sh.wkey[0]; bpos = sh.wpos[0];
+#pragma unroll
+        for (int w = 1; w < NT / 64; ++w) {
+            const unsigned long long ok = sh.wkey[w];
+            if (ok > best) { best = ok; bpos = sh.wpos[w]; }
+        }
+        const float gbest = __uint_as_float((unsigned)(best >> 32));
+        const int vstar = (int)(0xFFFFFFFFu - (unsigned)(best & 0xFFFFFFFFull));
+        const int pstar = bpos;
+        const int last = nR - 1;
+        __syncthreads();   // everyone has read sh.f/cnt/valid/wkey and the patch list of this step
         if (tid == 0) {
-            int nneed = 0;
-            if (!done) {
-                for (int k = 0; k < K; ++k)
-                    if (s_cnt[k] < s_cap[k] && !s_valid[k]) st.need[nneed++] = k;
-            }
-            st.nneed = nneed;
-            if (nneed > 0) {
-                const int tiles = (nR + RCD_TILE - 1) / RCD_TILE;
-                int C = (st.target_items + tiles - 1) / tiles;
-                C = C < 1 ? 1 : (C > RCD_CMAX ? RCD_CMAX : C);
-                int rpc = (n + C - 1) / C;
-                rpc = (rpc + 15) & ~15;
-                st.rpc = rpc;
-                st.C = (n + rpc - 1) / rpc;
-                st.stat_sweeps += 1;
-                st.stat_entries += (long long)nR * n;
-                st.stat_computed += (long long)nneed * nR;
-            }
-            st.stat_steps += t - st.t;
-            st.stat_useful += useful;
-            st.nR = nR;
-            st.t = t;
-            st.done = done;
-            for (int k = 0; k < K; ++k) {
-                st.f[k] = s_f[k];
-                st.cnt[k] = s_cnt[k];
-                st.valid[k] = s_valid[k];
-            }
+            const int np = sh.npatch;
+            const int src_star = effective_pos(sh, np, pstar);
+            const int src_last = effective_pos(sh, np, last);
+            const int u = sh.nupd;
+            sh.ujs[u] = js; sh.usrc[u] = src_star; sh.uv[u] = vstar; sh.ut[u] = t;
+            sh.nupd = u + 1;
+            // drop what the list said about the two positions, then: p* shows the last column
+            int m = 0;
+            for (int i = 0; i < np; ++i)
+                if (sh.ppos[i] != pstar && sh.ppos[i] != last) { sh.ppos[m] = sh.ppos[i]; sh.psrc[m] = sh.psrc[i]; ++m; }
+            if (pstar != last) { sh.ppos[m] = pstar; sh.psrc[m] = src_last; ++m; }
+            sh.npatch = m;
+            sh.cnt[js] += 1;
+            sh.f[js] += (double)gbest;
+            sh.valid[js] = 0;
         }
-    } else if (tid == 0) {
-        st.nneed = 0;
+        useful += nR;
+        nR = last;
+        ++t;
+        __syncthreads();
     }
 
-    // The last workgroup to get here lays out the next sweep over all classes.
-    __threadfence();
-    __syncthreads();
+    // ---- hand the steps taken and the displaced columns to the apply kernel
+    if (tid < RCD_KMAX) {
+        st.ujs[tid] = sh.ujs[tid];
+        st.usrc[tid] = sh.usrc[tid];
+        st.uv[tid] = sh.uv[tid];
+        st.ut[tid] = sh.ut[tid];
+        st.ppos[tid] = sh.ppos[tid];
+        st.psrc[tid] = sh.psrc[tid];
+    }
+    // publish the state and what the next sweep must do
     if (tid == 0) {
-        const int ticket = atomicAdd(&plan->arrive, 1);
-        s_last_arrival = (ticket == (int)gridDim.x - 1);
-    }
-    __syncthreads();
-    if (s_last_arrival && tid == 0) {
-        __threadfence();
-        int32_t *ip = reinterpret_cast<int32_t *>(plan + 1);
-        int32_t *tp = ip + (plan->ncls + 1);
-        int items = 0, tiles_total = 0, ndone = 0;
-        const int ncls = plan->ncls;
-        for (int c = 0; c < ncls; ++c) {
-            const RcdClass &o = classes[c];
-            const int nneed = __atomic_load_n(&o.nneed, __ATOMIC_RELAXED);
-            ip[c] = items;
-            tp[c] = tiles_total;
-            if (nneed > 0) {
-                const int tiles = (__atomic_load_n(&o.nR, __ATOMIC_RELAXED) + RCD_TILE - 1) / RCD_TILE;
-                items += tiles * __atomic_load_n(&o.C, __ATOMIC_RELAXED);
-                tiles_total += tiles;
-            }
-            ndone += __atomic_load_n(&o.done, __ATOMIC_RELAXED) ? 1 : 0;
+        int nneed = 0;
+        if (!done) {
+            for (int k = 0; k < K; ++k)
+                if (sh.cnt[k] < sh.cap[k] && !sh.valid[k]) st.need[nneed++] = k;
         }
-        ip[ncls] = items;
-        tp[ncls] = tiles_total;
-        plan->items = items;
-        plan->tiles = tiles_total;
-        plan->ndone = ndone;
-        plan->arrive = 0;
+        dev_store((gi32)&st.nneed, nneed);
+        if (nneed > 0) {
+            const int tiles = (nR + RCD_TILE - 1) / RCD_TILE;
+            int C = (st.target_items + tiles - 1) / tiles;
+            C = C < 1 ? 1 : (C > RCD_CMAX ? RCD_CMAX : C);
+            int rpc = (n + C - 1) / C;
+            rpc = (rpc + RCD_ROW_ALIGN - 1) & ~(RCD_ROW_ALIGN - 1);
+            st.rpc = rpc;
+            dev_store((gi32)&st.C, (n + rpc - 1) / rpc);
+            st.stat_sweeps += 1;
+            st.stat_entries += (long long)nR * n;
+            st.stat_computed += (long long)nneed * nR;
+        }
+        st.stat_steps += t - t0;
+        st.stat_useful += useful;
+        st.stat_ticks += wall_clock64() - tick0;
+        st.nupd = sh.nupd;
+        st.npatch = sh.npatch;
+        st.apply_round = st.apply_round + 1;
+        dev_store((gi32)&st.nR, nR);
+        st.t = t;
+        dev_store((gi32)&st.done, done);
+        for (int k = 0; k < K; ++k) {
+            st.f[k] = sh.f[k];
+            st.cnt[k] = sh.cnt[k];
+            st.valid[k] = sh.valid[k];
+        }
     }
-    (void)target_total;
+}
+
+// Lay out the next round's sweep over all classes into plan buffer `next` and
+// retire buffer `cur_buf`.  Called by exactly one thread, after the last arrival.
+__device__ __forceinline__ void write_plan(RcdClass *classes, RcdPlan *plans, int cur_buf, int next)
+{
+    const int ncls = plans[0].ncls;
+    int32_t *ip = plan_prefix(plans, next);
+    int items = 0, ndone = 0, nactive = 0;
+    for (int c = 0; c < ncls; ++c) {
+        const RcdClass &o = classes[c];
+        const int nneed = dev_load((gci32)&o.nneed);
+        ip[c] = items;
+        if (nneed > 0) {
+            const int tiles = (dev_load((gci32)&o.nR) + RCD_TILE - 1) / RCD_TILE;
+            items += tiles * dev_load((gci32)&o.C);
+            nactive += 1;
+        }
+        ndone += dev_load((gci32)&o.done) ? 1 : 0;
+    }
+    ip[ncls] = items;
+    plans[next].items = items;
+    plans[next].nactive = nactive;
+    plans[next].ndone = ndone;
+    plans[next].arrive = 0;
+    if (cur_buf >= 0) {
+        // late workgroups of this launch only ever see "nothing to do" here
+        plans[cur_buf].items = 0;
+        plans[cur_buf].nactive = 0;
+        plans[cur_buf].ndone = ndone;
+    }
+}
+
+} // namespace
+
+// Bootstrap (and the whole loop when there is nothing to sweep): one workgroup
+// per class runs the steps and the last one to finish writes plan buffer 0.
+extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
+rcd_k_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
+{
+    __shared__ StepShared sh;
+    __shared__ int s_flag;
+    class_steps<RCD_STEP_THREADS>(classes[blockIdx.x], sh);
+    if (arrive_last(&plans[1].arrive, (int)gridDim.x, &s_flag) && threadIdx.x == 0) {
+        plans[1].arrive = 0;
+        write_plan(classes, plans, -1, 0);
+    }
+}
+
+// One round for every class of the group, in a single launch:
+//   1. sweep: every workgroup computes one (class, tile, row chunk) of partial gains
+//   2. the workgroup that completes a tile adds its chunks in order -> gain
+//   3. the workgroup that completes a class runs that class's greedy steps
+//      (while other classes are still being swept)
+//   4. the workgroup that completes the last class writes the next round's plan
+// Completion is detected with arrival counters; nothing ever waits.  Launch r reads plan buffer r&1 and writes
+// the other one.
+extern "C" __global__ void __launch_bounds__(RCD_SWEEP_THREADS)
+rcd_k_round(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int buf)
+{
+    __shared__ float4 lds[RCD_SWEEP_WAVES * 4 * 64];
+    __shared__ StepShared sh;
+    __shared__ int s_flag;
+    const RcdPlan *plan = plans + buf;
+    const int item = blockIdx.x;
+    if (item >= plan->items) return;
+    const int ncls = plans[0].ncls;
+    const int32_t *prefix = plan_prefix(plans, buf);
+    const int c = ncls > 1 ? find_class(prefix, ncls, item) : 0;
+    RcdClass &st = classes[c];
+    const int local = item - prefix[c];
+    const int tiles = (st.nR + RCD_TILE - 1) / RCD_TILE;
+    const int tile = local % tiles;
+    const int chunk = local / tiles;
+    const int nneed = st.nneed;
+    if (nneed <= 1) sweep_body<1>(st, tile, chunk, lds);
+    else if (nneed == 2) sweep_body<2>(st, tile, chunk, lds);
+    else if (nneed == 3) sweep_body<3>(st, tile, chunk, lds);
+    else if (nneed == 4) sweep_body<4>(st, tile, chunk, lds);
+    else if (nneed <= 6) sweep_body<6>(st, tile, chunk, lds);
+    else if (nneed <= 8) sweep_body<8>(st, tile, chunk, lds);
+    else if (nneed <= 12) sweep_body<12>(st, tile, chunk, lds);
+    else sweep_body<16>(st, tile, chunk, lds);
+
+    // ---- 2. last chunk of this tile?
+    const int tid = threadIdx.x;
+    const int C = st.C;
+    if (!arrive_last(&st.tilecnt[tile], C, &s_flag)) return;
+    if (tid < RCD_TILE) {
+        const int ld = st.ld, K = st.K;
+        const int col = tile * RCD_TILE + tid;
+        const gcf32 part = (gcf32)st.part + col;
+        const size_t kstride = (size_t)K * ld;
+        for (int i = 0; i < nneed; ++i) {
+            const int k = st.need[i];
+            const gcf32 p = part + (size_t)k * ld;
+            float g = 0.f;
+            int ch = 0;
+            for (; ch + 8 <= C; ch += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = dev_load(p + (size_t)(ch + u) * kstride);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) g += v[u];
+            }
+            for (; ch < C; ++ch) g += dev_load(p + (size_t)ch * kstride);
+            dev_store((gf32)st.gain + (size_t)k * ld + col, g);
+        }
+        if (tid == 0) st.tilecnt[tile] = 0;
+    }
+    // ---- 3. last tile of this class?
+    if (!arrive_last(&st.tiles_done, tiles, &s_flag)) return;
+    if (tid == 0) st.tiles_done = 0;
+    class_steps<RCD_SWEEP_THREADS>(st, sh);
+    // ---- 4. last active class of the group?
+    if (arrive_last(&plans[buf].arrive, plan->nactive, &s_flag) && tid == 0)
+        write_plan(classes, plans, buf, buf ^ 1);
+}
+
+// Applies what the step loops of the last round decided.  grid = (row blocks, ncls),
+// one thread per row j of the class:
+//   coverage:  cur_js(j) = max(cur_js(j), S(j, v*)) for every step taken
+//   compaction: the column at (dead) position psrc moves to live position ppos
+// All loads come before the stores; sources of moves are dead positions that
+// nothing writes, and the coverage reads use positions as they were before the
+// moves, so the order inside a thread is all that matters.  Row block 0 also
+// moves the gains and perm entries and writes the caller's arrays.
+extern "C" __global__ void __launch_bounds__(256)
+rcd_k_apply(RcdClass *__restrict__ classes, int round_no)
+{
+    RcdClass &st = classes[blockIdx.y];
+    if (st.apply_round != round_no) return;
+    const int nupd = st.nupd, npatch = st.npatch;
+    const int n = st.n, ld = st.ld, K = st.K;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const gf32 M = (gf32)st.M;
+    if (j < n) {
+        float sv[RCD_KMAX], cv[RCD_KMAX], mv[RCD_KMAX];
+        const gf32 row = M + (size_t)j * ld;
+#pragma unroll
+        for (int i = 0; i < RCD_KMAX; ++i)
+            if (i < nupd) {
+                sv[i] = row[st.usrc[i]];
+                cv[i] = ((gf32)st.cur)[(size_t)st.ujs[i] * ld + j];
+            }
+#pragma unroll
+        for (int i = 0; i < RCD_KMAX; ++i)
+            if (i < npatch) mv[i] = row[st.psrc[i]];
+#pragma unroll
+        for (int i = 0; i < RCD_KMAX; ++i)
+            if (i < nupd && sv[i] > cv[i]) ((gf32)st.cur)[(size_t)st.ujs[i] * ld + j] = sv[i];
+#pragma unroll
+        for (int i = 0; i < RCD_KMAX; ++i)
+            if (i < npatch) row[st.ppos[i]] = mv[i];
+    }
+    if (blockIdx.x == 0) {
+        const int tid = threadIdx.x;
+        for (int e = tid; e < npatch * (K + 1); e += 256) {
+            const int i = e / (K + 1), k = e % (K + 1);
+            const int dpos = st.ppos[i], spos = st.psrc[i];
+            if (k < K) st.gain[(size_t)k * ld + dpos] = st.gain[(size_t)k * ld + spos];
+            else st.perm[dpos] = st.perm[spos];
+        }
+        if (tid < nupd) {
+            const int v = st.uv[tid];
+            const int oi = st.out_index ? st.out_index[v] : v;
+            st.assign_out[oi] = st.ujs[tid];
+            if (st.order_out) st.order_out[oi] = st.ut[tid];
+        }
+    }
 }
 
 // Initial state of a group of classes: cur = 0 (f of the empty set is 0),
@@ -391,6 +569,7 @@ extern "C" __global__ void rcd_k_init(const RcdClass *__restrict__ classes)
     const size_t ncur = (size_t)st.K * st.ld;
     for (size_t i = i0; i < ncur; i += stride) st.cur[i] = 0.f;
     for (int i = i0; i < st.ld; i += stride) st.perm[i] = i;
+    for (int i = i0; i < st.ld / RCD_TILE; i += stride) st.tilecnt[i] = 0;
     for (int i = i0; i < st.n; i += stride) {
         const int oi = st.out_index ? st.out_index[i] : i;
         st.assign_out[oi] = -1;

@@ -20,11 +20,11 @@ static_assert(RCD_KMAX == RCD_MAX_K, "public and internal block limits differ");
 namespace {
 
 thread_local char g_hip_err[320] = "";
-thread_local int64_t g_stats[6] = {0, 0, 0, 0, 0, 0};
-thread_local RcdPlan *g_pinned = nullptr;   // 2 progress slots, pinned, never freed
+thread_local int64_t g_stats[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+thread_local RcdPlan *g_pinned = nullptr;   // 2 progress slots of 2 plan headers, pinned, never freed
 // optional per-kernel timing (HIP events between the launches of a round)
 thread_local int g_profile_on = 0;
-thread_local double g_prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // ms: steps, sweep, finalize; rounds; similarity ms
+thread_local double g_prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // ms: steps, sweep, -, rounds, similarity ms
 thread_local std::vector<hipEvent_t> g_prof_ev[2];
 
 #define HIP_TRY(expr)                                                                      \
@@ -78,13 +78,14 @@ size_t class_state_bytes(int64_t n, int K, bool stored)
     b += up256((size_t)K * ld * 4);              // cur
     b += up256((size_t)RCD_CMAX * K * ld * 4);   // part
     b += up256((size_t)K * ld * 4);              // gain
+    b += up256(ld / RCD_TILE * 4);               // tilecnt
     b += up256(ld * 4);                          // perm
     return b;
 }
 
 size_t group_fixed_bytes(int ncls, int K)
 {
-    return up256((size_t)ncls * sizeof(RcdClass)) + up256(sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4) +
+    return up256((size_t)ncls * sizeof(RcdClass)) + up256(2 * sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4) +
            up256((size_t)ncls * K * sizeof(double));
 }
 
@@ -108,6 +109,7 @@ bool carve_class(Carver &cv, RcdClass &c, int64_t n, int K, const int64_t *cap, 
     c.cur = cv.take<float>((size_t)K * ld);
     c.part = cv.take<float>((size_t)RCD_CMAX * K * ld);
     c.gain = cv.take<float>((size_t)K * ld);
+    c.tilecnt = cv.take<int32_t>(ld / RCD_TILE);
     c.perm = cv.take<int32_t>(ld);
     int64_t total = 0;
     for (int k = 0; k < K; ++k) {
@@ -132,7 +134,7 @@ void choose_chunks(int n, int nR, int target_items, int *C, int *rpc)
     int c = (target_items + tiles - 1) / tiles;
     c = c < 1 ? 1 : (c > RCD_CMAX ? RCD_CMAX : c);
     int r = (n + c - 1) / c;
-    r = (r + 15) & ~15;
+    r = (r + RCD_ROW_ALIGN - 1) & ~(RCD_ROW_ALIGN - 1);
     *rpc = r;
     *C = (n + r - 1) / r;
 }
@@ -141,7 +143,7 @@ int ensure_pinned()
 {
     if (!g_pinned) {
         void *p = nullptr;
-        HIP_TRY(hipHostMalloc(&p, 2 * sizeof(RcdPlan), hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc(&p, 4 * sizeof(RcdPlan), hipHostMallocDefault));
         g_pinned = (RcdPlan *)p;
     }
     return RCD_OK;
@@ -155,30 +157,37 @@ int run_group(Group &g, hipStream_t stream)
     RCD_TRY(ensure_pinned());
     const int target_total = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
     const int per_class = std::max(1, target_total / ncls);
-    int items_ub = 0, tiles_ub = 0;
+    int items_ub = 0;
     for (RcdClass &c : g.host) {
         c.target_items = per_class;
         items_ub += sweep_items_bound(c);
-        tiles_ub += (c.n + RCD_TILE - 1) / RCD_TILE;
     }
     RcdPlan plan0;
     memset(&plan0, 0, sizeof plan0);
     plan0.ncls = ncls;
-    // the validation kernels may already have raised plan->bad: keep it
-    HIP_TRY(hipMemcpyAsync(&g.plan_dev->ncls, &plan0.ncls, sizeof(int32_t) * 5, hipMemcpyHostToDevice, stream));
+    // the validation kernels may already have raised plans[0].bad: keep it
+    HIP_TRY(hipMemcpyAsync(&g.plan_dev[0].ncls, &plan0.ncls, sizeof(int32_t) * 5, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(&g.plan_dev[1], &plan0, sizeof plan0, hipMemcpyHostToDevice, stream));
     HIP_TRY(hipMemcpyAsync(g.classes_dev, g.host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
     hipLaunchKernelGGL(rcd_k_init, dim3(64, ncls), dim3(256), 0, stream, g.classes_dev);
+    int max_n = 0;
+    for (const RcdClass &c : g.host) max_n = std::max(max_n, c.n);
+    const dim3 apply_grid((unsigned)((max_n + 255) / 256), (unsigned)ncls);
+    // step loop number 1 (the bootstrap) and its apply; step loop r+2 runs inside round r
+    hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev, g.plan_dev);
+    hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g.classes_dev, 1);
 
     hipEvent_t ev[2];
     HIP_TRY(hipEventCreateWithFlags(&ev[0], hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&ev[1], hipEventDisableTiming));
     const int rounds = env_int("RCD_ROUNDS_PER_BATCH", 16, 1, 1024);
-    int64_t launches = 1;
+    int64_t launches = 3;
+    int round_no = 0;
     int rc = RCD_OK;
     const bool prof = g_profile_on != 0;
     if (prof) {
         for (int s = 0; s < 2; ++s)
-            while ((int)g_prof_ev[s].size() < 3 * rounds + 1) {
+            while ((int)g_prof_ev[s].size() < 2 * rounds + 1) {
                 hipEvent_t e;
                 HIP_TRY(hipEventCreate(&e));
                 g_prof_ev[s].push_back(e);
@@ -190,9 +199,8 @@ int run_group(Group &g, hipStream_t stream)
         std::vector<hipEvent_t> &e = g_prof_ev[batch & 1];
         for (int r = 0; r < rounds; ++r) {
             float ms = 0.f;
-            if (hipEventElapsedTime(&ms, e[3 * r], e[3 * r + 1]) == hipSuccess) g_prof[0] += ms;
-            if (hipEventElapsedTime(&ms, e[3 * r + 1], e[3 * r + 2]) == hipSuccess) g_prof[1] += ms;
-            if (hipEventElapsedTime(&ms, e[3 * r + 2], e[3 * r + 3]) == hipSuccess) g_prof[2] += ms;
+            if (hipEventElapsedTime(&ms, e[2 * r], e[2 * r + 1]) == hipSuccess) g_prof[1] += ms;
+            if (hipEventElapsedTime(&ms, e[2 * r + 1], e[2 * r + 2]) == hipSuccess) g_prof[0] += ms;
         }
         g_prof[3] += rounds;
     };
@@ -210,24 +218,21 @@ int run_group(Group &g, hipStream_t stream)
         std::vector<hipEvent_t> *pe = prof ? &g_prof_ev[b & 1] : nullptr;
         if (pe) (void)hipEventRecord((*pe)[0], stream);
         for (int r = 0; r < rounds; ++r) {
-            hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev,
-                               g.plan_dev, 0);
-            if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
-            hipLaunchKernelGGL(rcd_k_sweep, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream,
-                               (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
-            if (pe) (void)hipEventRecord((*pe)[3 * r + 2], stream);
-            hipLaunchKernelGGL(rcd_k_finalize, dim3(tiles_ub), dim3(RCD_TILE), 0, stream,
-                               (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
-            if (pe) (void)hipEventRecord((*pe)[3 * r + 3], stream);
+            hipLaunchKernelGGL(rcd_k_round, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
+                               g.plan_dev, round_no & 1);
+            ++round_no;
+            if (pe) (void)hipEventRecord((*pe)[2 * r + 1], stream);
+            hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g.classes_dev, round_no + 1);
+            if (pe) (void)hipEventRecord((*pe)[2 * r + 2], stream);
         }
-        launches += 3 * (int64_t)rounds;
+        launches += 2 * (int64_t)rounds;
         hipError_t le = hipGetLastError();
         if (le != hipSuccess) {
             snprintf(g_hip_err, sizeof g_hip_err, "kernel launch -> %s", hipGetErrorString(le));
             rc = RCD_ERR_HIP;
             break;
         }
-        hipError_t e1 = hipMemcpyAsync(&g_pinned[b & 1], g.plan_dev, sizeof(RcdPlan), hipMemcpyDeviceToHost, stream);
+        hipError_t e1 = hipMemcpyAsync(&g_pinned[2 * (b & 1)], g.plan_dev, 2 * sizeof(RcdPlan), hipMemcpyDeviceToHost, stream);
         hipError_t e2 = hipEventRecord(ev[b & 1], stream);
         if (e1 != hipSuccess || e2 != hipSuccess) {
             snprintf(g_hip_err, sizeof g_hip_err, "progress readback -> %s",
@@ -243,9 +248,9 @@ int run_group(Group &g, hipStream_t stream)
                 break;
             }
             if (prof) { read_events(b - 1); prof_done = b; }
-            const RcdPlan &seen = g_pinned[(b - 1) & 1];
-            if (seen.bad) { rc = RCD_ERR_BAD_SIMILARITY; last_batch = b; break; }
-            if (seen.ndone >= ncls) { last_batch = b; break; }
+            const RcdPlan *seen = &g_pinned[2 * ((b - 1) & 1)];
+            if (seen[0].bad) { rc = RCD_ERR_BAD_SIMILARITY; last_batch = b; break; }
+            if (std::max(seen[0].ndone, seen[1].ndone) >= ncls) { last_batch = b; break; }
         }
     }
     hipError_t es = hipStreamSynchronize(stream);
@@ -268,6 +273,7 @@ int run_group(Group &g, hipStream_t stream)
         g_stats[2] += c.stat_entries;
         g_stats[3] += c.stat_useful;
         g_stats[5] += c.stat_computed;
+        g_stats[6] += c.stat_ticks;
     }
     g_stats[4] += launches + 1;
     return RCD_OK;
@@ -276,7 +282,7 @@ int run_group(Group &g, hipStream_t stream)
 bool carve_group_fixed(Carver &cv, Group &g, int ncls, int K)
 {
     g.classes_dev = cv.take<RcdClass>((size_t)ncls);
-    g.plan_dev = reinterpret_cast<RcdPlan *>(cv.take<char>(sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4));
+    g.plan_dev = reinterpret_cast<RcdPlan *>(cv.take<char>(2 * sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4));
     g.obj_dev = cv.take<double>((size_t)ncls * K);
     g.K = K;
     return !cv.fail;
@@ -345,9 +351,9 @@ const char *rcd_strerror(int status)
 
 const char *rcd_last_hip_error(void) { return g_hip_err; }
 
-void rcd_last_stats(int64_t *out6_host)
+void rcd_last_stats(int64_t *out8_host)
 {
-    if (out6_host) memcpy(out6_host, g_stats, sizeof g_stats);
+    if (out8_host) memcpy(out8_host, g_stats, sizeof g_stats);
 }
 
 void rcd_profile(int enable)
@@ -448,27 +454,27 @@ int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const flo
     c.target_items = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
     choose_chunks(c.n, c.nR, c.target_items, &c.C, &c.rpc);
     const int tiles = (c.n + RCD_TILE - 1) / RCD_TILE;
-    struct { RcdPlan p; int32_t pre[4]; } plan;
+    struct { RcdPlan p[2]; int32_t pre[4]; } plan;
     memset(&plan, 0, sizeof plan);
-    plan.p.ncls = 1;
-    plan.p.items = tiles * c.C;
-    plan.p.tiles = tiles;
-    plan.pre[0] = 0; plan.pre[1] = plan.p.items; plan.pre[2] = 0; plan.pre[3] = tiles;
+    plan.p[0].ncls = plan.p[1].ncls = 1;
+    plan.p[0].items = tiles * c.C;
+    plan.p[0].nactive = 1;
+    plan.pre[0] = 0; plan.pre[1] = plan.p[0].items;
     HIP_TRY(hipMemcpyAsync(g.plan_dev, &plan, sizeof plan, hipMemcpyHostToDevice, stream));
     HIP_TRY(hipMemcpyAsync(g.classes_dev, g.host.data(), sizeof(RcdClass), hipMemcpyHostToDevice, stream));
     hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
                        (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
     hipLaunchKernelGGL(rcd_k_import_cur, dim3((unsigned)((n + 255) / 256), K), dim3(256), 0, stream,
                        (const RcdClass *)g.classes_dev, cur_dev);
-    hipLaunchKernelGGL(rcd_k_sweep, dim3(plan.p.items), dim3(RCD_SWEEP_THREADS), 0, stream,
-                       (const RcdClass *)g.classes_dev, (const RcdPlan *)g.plan_dev);
-    hipLaunchKernelGGL(rcd_k_finalize, dim3(tiles), dim3(RCD_TILE), 0, stream, (const RcdClass *)g.classes_dev,
-                       (const RcdPlan *)g.plan_dev);
+    HIP_TRY(hipMemsetAsync(c.tilecnt, 0, (size_t)(c.ld / RCD_TILE) * 4, stream));
+    // total = 0: after the sweep the class's step loop finds nothing to do
+    hipLaunchKernelGGL(rcd_k_round, dim3(plan.p[0].items), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
+                       g.plan_dev, 0);
     hipLaunchKernelGGL(rcd_k_export_gains, dim3((unsigned)((n + 255) / 256), K), dim3(256), 0, stream,
                        (const RcdClass *)g.classes_dev, gains_dev);
     HIP_TRY(hipGetLastError());
     RcdPlan back;
-    HIP_TRY(hipMemcpyAsync(&back, g.plan_dev, sizeof back, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipMemcpyAsync(&back, &g.plan_dev[0], sizeof back, hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
     if (back.bad) return RCD_ERR_BAD_SIMILARITY;
     return RCD_OK;
@@ -511,7 +517,7 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     if (!carve_class(cv, c, n, K, cap_host, stored)) return RCD_ERR_WORKSPACE;
     c.assign_out = assign_dev;
     c.order_out = order_dev;
-    HIP_TRY(hipMemsetAsync(g.plan_dev, 0, sizeof(RcdPlan), stream));
+    HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
     hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
                        (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
     RCD_TRY(run_group(g, stream));
@@ -603,7 +609,7 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
             g.host.resize(live);
             std::vector<int> cls_of(live);
             int gi = 0;
-            HIP_TRY(hipMemsetAsync(g.plan_dev, 0, sizeof(RcdPlan), stream));
+            HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
             hipEvent_t sim_ev[2] = {nullptr, nullptr};
             if (g_profile_on) {
                 HIP_TRY(hipEventCreate(&sim_ev[0]));

@@ -1,16 +1,18 @@
 // Device-resident state of the class greedy (Algorithm 1, inner loop) shared by
 // the host orchestration and the kernels.  One RcdClass per class that is being
 // advanced; all classes of a group move in lock step, one "round" at a time:
-//   steps kernel   - runs as many greedy steps as the finished gain rows allow
-//   sweep kernel   - recomputes the gain rows that went stale, for all classes
-//   finalize kernel- adds the row-chunk partial sums in a fixed order
+//   sweep  - recomputes the gain rows that went stale
+//   steps  - runs as many greedy steps as the current gain rows allow
+// Both happen inside one launch per round (see rcd_k_round).
 #pragma once
 #include <stdint.h>
 
 #define RCD_KMAX 16          // must equal RCD_MAX_K of the public header
 #define RCD_TILE 256         // candidate columns per sweep tile (64 lanes x 4)
 #define RCD_CMAX 32          // most row chunks a class's sweep is split into
-#define RCD_SWEEP_THREADS 256
+#define RCD_SWEEP_WAVES 8     // waves of a sweep workgroup: each takes an eighth of the chunk's rows
+#define RCD_SWEEP_THREADS (64 * RCD_SWEEP_WAVES)
+#define RCD_ROW_ALIGN (4 * RCD_SWEEP_WAVES)   // rows per chunk are a multiple of this (4-row unroll per wave)
 #define RCD_STEP_THREADS 1024
 
 struct RcdClass {
@@ -20,6 +22,7 @@ struct RcdClass {
     float *part;         // RCD_CMAX x K x ld partial gain sums per row chunk
     float *gain;         // K x ld finished gains, indexed by column position
     int32_t *perm;       // ld: original (class-local) index held by column p
+    int32_t *tilecnt;    // ld/RCD_TILE arrival counters of the sweep's row chunks, per tile
     int32_t *assign_out; // caller's arrays (global indexing through out_index)
     int32_t *order_out;  // nullable
     const int32_t *out_index; // nullable: position of local sample v in the caller's arrays
@@ -35,22 +38,31 @@ struct RcdClass {
     int32_t done;
     int32_t nneed;       // blocks whose gains the next sweep must produce
     int32_t C, rpc;      // row chunks of the next sweep, rows per chunk
+    int32_t tiles_done;  // arrival counter of the sweep's finished tiles
     int32_t need[RCD_KMAX];
     int32_t cnt[RCD_KMAX];
     int32_t cap[RCD_KMAX];
     int32_t valid[RCD_KMAX];
     double f[RCD_KMAX];  // running f(A_k): sum of accepted gains
+    // decisions of the last step loop, consumed by the apply kernel of the same round
+    int32_t apply_round; // number of step loops run so far = round the lists belong to
+    int32_t nupd, npatch;
+    int32_t ujs[RCD_KMAX], usrc[RCD_KMAX], uv[RCD_KMAX], ut[RCD_KMAX];   // block, column position, sample, step
+    int32_t ppos[RCD_KMAX], psrc[RCD_KMAX];   // live position <- dead position
     // ---- counters
     int64_t stat_steps, stat_sweeps, stat_entries, stat_useful, stat_computed;
+    int64_t stat_ticks;  // 100 MHz ticks spent inside the step loops
 };
 
+// Work layout of one round.  Two of these are kept (launch r reads buffer r&1
+// and writes the other), followed in memory by two int32 prefix[ncls+1] arrays:
+// prefix[c] = first sweep workgroup of class c.
 struct RcdPlan {
-    int32_t ncls;
-    int32_t arrive;      // arrival counter of the steps kernel's workgroups
+    int32_t ncls;        // classes in the group (buffer 0's copy is the one read)
+    int32_t arrive;      // arrival counter of classes that finished their steps
     int32_t items;       // sweep workgroups with work this round
-    int32_t tiles;       // finalize workgroups with work this round
+    int32_t nactive;     // classes with work this round
     int32_t ndone;       // classes finished
-    int32_t bad;         // set by validation kernels (bad label / similarity out of range)
+    int32_t bad;         // set by validation kernels (buffer 0 only)
     int32_t pad[2];
-    // followed in memory by: int32 item_prefix[ncls+1]; int32 tile_prefix[ncls+1]
 };
