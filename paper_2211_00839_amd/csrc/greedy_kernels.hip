@@ -361,11 +361,11 @@ __device__ __forceinline__ void class_steps(RcdClass &st, StepShared &sh)
         }
         dev_store((gi32)&st.nneed, nneed);
         if (nneed > 0) {
-            const int tiles = (nR + RCD_TILE - 1) / RCD_TILE;
+            const int tiles = (nR + st.tw - 1) / st.tw;
             int C = (st.target_items + tiles - 1) / tiles;
             C = C < 1 ? 1 : (C > RCD_CMAX ? RCD_CMAX : C);
             int rpc = (n + C - 1) / C;
-            rpc = (rpc + RCD_ROW_ALIGN - 1) & ~(RCD_ROW_ALIGN - 1);
+            rpc = (rpc + st.row_align - 1) / st.row_align * st.row_align;
             st.rpc = rpc;
             dev_store((gi32)&st.C, (n + rpc - 1) / rpc);
             st.stat_sweeps += 1;
@@ -401,7 +401,7 @@ __device__ __forceinline__ void write_plan(RcdClass *classes, RcdPlan *plans, in
         const int nneed = dev_load((gci32)&o.nneed);
         ip[c] = items;
         if (nneed > 0) {
-            const int tiles = (dev_load((gci32)&o.nR) + RCD_TILE - 1) / RCD_TILE;
+            const int tiles = (dev_load((gci32)&o.nR) + o.tw - 1) / o.tw;
             items += tiles * dev_load((gci32)&o.C);
             nactive += 1;
         }
@@ -418,6 +418,48 @@ __device__ __forceinline__ void write_plan(RcdClass *classes, RcdPlan *plans, in
         plans[cur_buf].nactive = 0;
         plans[cur_buf].ndone = ndone;
     }
+}
+
+// What follows a workgroup's sweep item (steps 2-4 of a round, see rcd_k_round).
+// NT threads in the workgroup, TW columns per tile.
+template <int NT, int TW>
+__device__ __forceinline__ void round_tail(RcdClass &st, RcdClass *classes, RcdPlan *plans, int buf, int tile,
+                                           int tiles, StepShared &sh, int *s_flag)
+{
+    // ---- 2. last chunk of this tile?  then add the chunks' partial sums in order
+    const int tid = threadIdx.x;
+    const int C = st.C;
+    const int nneed = st.nneed;
+    if (!arrive_last(&st.tilecnt[tile], C, s_flag)) return;
+    if (tid < TW) {
+        const int ld = st.ld, K = st.K;
+        const int col = tile * TW + tid;
+        const gcf32 part = (gcf32)st.part + col;
+        const size_t kstride = (size_t)K * ld;
+        for (int i = 0; i < nneed; ++i) {
+            const int k = st.need[i];
+            const gcf32 p = part + (size_t)k * ld;
+            float g = 0.f;
+            int ch = 0;
+            for (; ch + 8 <= C; ch += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = dev_load(p + (size_t)(ch + u) * kstride);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) g += v[u];
+            }
+            for (; ch < C; ++ch) g += dev_load(p + (size_t)ch * kstride);
+            dev_store((gf32)st.gain + (size_t)k * ld + col, g);
+        }
+        if (tid == 0) st.tilecnt[tile] = 0;
+    }
+    // ---- 3. last tile of this class?  then run the class's greedy steps
+    if (!arrive_last(&st.tiles_done, tiles, s_flag)) return;
+    if (tid == 0) st.tiles_done = 0;
+    class_steps<NT>(st, sh);
+    // ---- 4. last active class of the group?  then lay out the next round
+    if (arrive_last(&plans[buf].arrive, plans[buf].nactive, s_flag) && tid == 0)
+        write_plan(classes, plans, buf, buf ^ 1);
 }
 
 } // namespace
@@ -471,39 +513,7 @@ rcd_k_round(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int buf
     else if (nneed <= 12) sweep_body<12>(st, tile, chunk, lds);
     else sweep_body<16>(st, tile, chunk, lds);
 
-    // ---- 2. last chunk of this tile?
-    const int tid = threadIdx.x;
-    const int C = st.C;
-    if (!arrive_last(&st.tilecnt[tile], C, &s_flag)) return;
-    if (tid < RCD_TILE) {
-        const int ld = st.ld, K = st.K;
-        const int col = tile * RCD_TILE + tid;
-        const gcf32 part = (gcf32)st.part + col;
-        const size_t kstride = (size_t)K * ld;
-        for (int i = 0; i < nneed; ++i) {
-            const int k = st.need[i];
-            const gcf32 p = part + (size_t)k * ld;
-            float g = 0.f;
-            int ch = 0;
-            for (; ch + 8 <= C; ch += 8) {
-                float v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = dev_load(p + (size_t)(ch + u) * kstride);
-#pragma unroll
-                for (int u = 0; u < 8; ++u) g += v[u];
-            }
-            for (; ch < C; ++ch) g += dev_load(p + (size_t)ch * kstride);
-            dev_store((gf32)st.gain + (size_t)k * ld + col, g);
-        }
-        if (tid == 0) st.tilecnt[tile] = 0;
-    }
-    // ---- 3. last tile of this class?
-    if (!arrive_last(&st.tiles_done, tiles, &s_flag)) return;
-    if (tid == 0) st.tiles_done = 0;
-    class_steps<RCD_SWEEP_THREADS>(st, sh);
-    // ---- 4. last active class of the group?
-    if (arrive_last(&plans[buf].arrive, plan->nactive, &s_flag) && tid == 0)
-        write_plan(classes, plans, buf, buf ^ 1);
+    round_tail<RCD_SWEEP_THREADS, RCD_TILE>(st, classes, plans, buf, tile, tiles, sh, &s_flag);
 }
 
 // Applies what the step loops of the last round decided.  grid = (row blocks, ncls),
@@ -569,7 +579,7 @@ extern "C" __global__ void rcd_k_init(const RcdClass *__restrict__ classes)
     const size_t ncur = (size_t)st.K * st.ld;
     for (size_t i = i0; i < ncur; i += stride) st.cur[i] = 0.f;
     for (int i = i0; i < st.ld; i += stride) st.perm[i] = i;
-    for (int i = i0; i < st.ld / RCD_TILE; i += stride) st.tilecnt[i] = 0;
+    for (int i = i0; i < st.ld / RCD_TILE_RC; i += stride) st.tilecnt[i] = 0;
     for (int i = i0; i < st.n; i += stride) {
         const int oi = st.out_index ? st.out_index[i] : i;
         st.assign_out[oi] = -1;

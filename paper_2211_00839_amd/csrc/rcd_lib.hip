@@ -14,6 +14,7 @@
 #include "greedy_kernels.hip"
 #include "similarity_kernels.hip"
 #include "split_kernels.hip"
+#include "recompute_kernels.hip"
 
 static_assert(RCD_KMAX == RCD_MAX_K, "public and internal block limits differ");
 
@@ -75,10 +76,11 @@ size_t class_state_bytes(int64_t n, int K, bool stored)
     const size_t ld = (size_t)pitch_of(n);
     size_t b = 0;
     if (stored) b += up256((size_t)n * ld * 4);
+    else b += up256((size_t)n * 4);              // squared row norms
     b += up256((size_t)K * ld * 4);              // cur
     b += up256((size_t)RCD_CMAX * K * ld * 4);   // part
     b += up256((size_t)K * ld * 4);              // gain
-    b += up256(ld / RCD_TILE * 4);               // tilecnt
+    b += up256(ld / RCD_TILE_RC * 4);            // tilecnt
     b += up256(ld * 4);                          // perm
     return b;
 }
@@ -106,10 +108,13 @@ bool carve_class(Carver &cv, RcdClass &c, int64_t n, int K, const int64_t *cap, 
     c.ld = (int)ld;
     c.K = K;
     if (stored) c.M = cv.take<float>((size_t)n * ld);
+    else c.sq = cv.take<float>((size_t)n);
+    c.tw = stored ? RCD_TILE : RCD_TILE_RC;
+    c.row_align = stored ? RCD_ROW_ALIGN : RCD_ROWS_RC;
     c.cur = cv.take<float>((size_t)K * ld);
     c.part = cv.take<float>((size_t)RCD_CMAX * K * ld);
     c.gain = cv.take<float>((size_t)K * ld);
-    c.tilecnt = cv.take<int32_t>(ld / RCD_TILE);
+    c.tilecnt = cv.take<int32_t>(ld / RCD_TILE_RC);
     c.perm = cv.take<int32_t>(ld);
     int64_t total = 0;
     for (int k = 0; k < K; ++k) {
@@ -124,7 +129,7 @@ bool carve_class(Carver &cv, RcdClass &c, int64_t n, int K, const int64_t *cap, 
 
 int sweep_items_bound(const RcdClass &c)
 {
-    const int tiles0 = (c.n + RCD_TILE - 1) / RCD_TILE;
+    const int tiles0 = (c.n + c.tw - 1) / c.tw;
     return std::min(RCD_CMAX * tiles0, c.target_items + tiles0);
 }
 
@@ -175,14 +180,36 @@ int run_group(Group &g, hipStream_t stream)
     const dim3 apply_grid((unsigned)((max_n + 255) / 256), (unsigned)ncls);
     // step loop number 1 (the bootstrap) and its apply; step loop r+2 runs inside round r
     hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev, g.plan_dev);
-    hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g.classes_dev, 1);
 
     hipEvent_t ev[2];
     HIP_TRY(hipEventCreateWithFlags(&ev[0], hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&ev[1], hipEventDisableTiming));
     const int rounds = env_int("RCD_ROUNDS_PER_BATCH", 16, 1, 1024);
+    // a group is homogeneous: all stored, or all recomputed from the same X
+    const RcdClass &first = g.host[0];
+    const bool recompute = first.mode == RCD_MODE_RECOMPUTE;
+    const int esz = first.dt == RCD_F32 ? 4 : 2;
+    const bool fast = recompute && (reinterpret_cast<uintptr_t>(first.X) & 15) == 0 &&
+                      ((first.ldx64 * esz) % 16) == 0 && ((int64_t)first.d * esz) % sim::ROWB == 0;
+    void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
+    void (*apply_rc)(RcdClass *, int) = nullptr;
+    if (recompute) {
+        if (first.dt == RCD_F32) {
+            round_rc = fast ? rcd_k_round_rc<float, true> : rcd_k_round_rc<float, false>;
+            apply_rc = rcd_k_apply_rc<float>;
+        } else {
+            round_rc = fast ? rcd_k_round_rc<__bf16, true> : rcd_k_round_rc<__bf16, false>;
+            apply_rc = rcd_k_apply_rc<__bf16>;
+        }
+    }
+    const dim3 apply_rc_grid((unsigned)((max_n + 3) / 4), (unsigned)ncls);
+    auto launch_apply = [&](int rn) {
+        if (recompute) hipLaunchKernelGGL(apply_rc, apply_rc_grid, dim3(256), 0, stream, g.classes_dev, rn);
+        else hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g.classes_dev, rn);
+    };
     int64_t launches = 3;
     int round_no = 0;
+    launch_apply(1);
     int rc = RCD_OK;
     const bool prof = g_profile_on != 0;
     if (prof) {
@@ -218,11 +245,15 @@ int run_group(Group &g, hipStream_t stream)
         std::vector<hipEvent_t> *pe = prof ? &g_prof_ev[b & 1] : nullptr;
         if (pe) (void)hipEventRecord((*pe)[0], stream);
         for (int r = 0; r < rounds; ++r) {
-            hipLaunchKernelGGL(rcd_k_round, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
-                               g.plan_dev, round_no & 1);
+            if (recompute)
+                hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), 0, stream, g.classes_dev, g.plan_dev,
+                                   round_no & 1);
+            else
+                hipLaunchKernelGGL(rcd_k_round, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
+                                   g.plan_dev, round_no & 1);
             ++round_no;
             if (pe) (void)hipEventRecord((*pe)[2 * r + 1], stream);
-            hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g.classes_dev, round_no + 1);
+            launch_apply(round_no + 1);
             if (pe) (void)hipEventRecord((*pe)[2 * r + 2], stream);
         }
         launches += 2 * (int64_t)rounds;
@@ -294,21 +325,49 @@ int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, 
     const float exp_scale = (float)(-1.4426950408889634 / (2.0 * (double)sigma2));
     const dim3 grid((unsigned)((ncols_pad + sim::BN - 1) / sim::BN), (unsigned)((n + sim::BM - 1) / sim::BM));
     const unsigned nblk = (unsigned)((n + 3) / 4);
+    const int esz = dt == RCD_F32 ? 4 : 2;
+    const bool fast = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ((ldx * esz) % 16) == 0 && (d * esz) % sim::ROWB == 0;
     if (dt == RCD_F32) {
         hipLaunchKernelGGL(sim::k_row_norms<float>, dim3(nblk), dim3(256), 0, stream, (const float *)X,
                            (long long)ldx, row_index, (int)n, (int)d, sq);
-        hipLaunchKernelGGL(sim::k_gram_rbf<float>, grid, dim3(sim::THREADS), 0, stream, (const float *)X,
-                           (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
-                           (long long)ld_s, ncols_pad);
+        auto kern = fast ? sim::k_gram_rbf<float, true> : sim::k_gram_rbf<float, false>;
+        hipLaunchKernelGGL(kern, grid, dim3(sim::THREADS), 0, stream, (const float *)X, (long long)ldx, row_index,
+                           (int)n, (int)d, (const float *)sq, exp_scale, S, (long long)ld_s, ncols_pad);
     } else {
         hipLaunchKernelGGL(sim::k_row_norms<__bf16>, dim3(nblk), dim3(256), 0, stream, (const __bf16 *)X,
                            (long long)ldx, row_index, (int)n, (int)d, sq);
-        hipLaunchKernelGGL(sim::k_gram_rbf<__bf16>, grid, dim3(sim::THREADS), 0, stream, (const __bf16 *)X,
-                           (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
-                           (long long)ld_s, ncols_pad);
+        auto kern = fast ? sim::k_gram_rbf<__bf16, true> : sim::k_gram_rbf<__bf16, false>;
+        hipLaunchKernelGGL(kern, grid, dim3(sim::THREADS), 0, stream, (const __bf16 *)X, (long long)ldx, row_index,
+                           (int)n, (int)d, (const float *)sq, exp_scale, S, (long long)ld_s, ncols_pad);
     }
     HIP_TRY(hipGetLastError());
     return RCD_OK;
+}
+
+int launch_row_norms(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, const int32_t *row_index, float *sq,
+                     hipStream_t stream)
+{
+    const unsigned nblk = (unsigned)((n + 3) / 4);
+    if (dt == RCD_F32)
+        hipLaunchKernelGGL(sim::k_row_norms<float>, dim3(nblk), dim3(256), 0, stream, (const float *)X, (long long)ldx,
+                           row_index, (int)n, (int)d, sq);
+    else
+        hipLaunchKernelGGL(sim::k_row_norms<__bf16>, dim3(nblk), dim3(256), 0, stream, (const __bf16 *)X,
+                           (long long)ldx, row_index, (int)n, (int)d, sq);
+    HIP_TRY(hipGetLastError());
+    return RCD_OK;
+}
+
+void set_recompute_source(RcdClass &c, const void *X, int dt, int64_t d, int64_t ldx, const int32_t *x_index,
+                          float sigma2)
+{
+    c.X = X;
+    c.x_index = x_index;
+    c.ldx64 = ldx;
+    c.d = (int)d;
+    c.ldx = (int)std::min<int64_t>(ldx, 0x7fffffff);
+    c.dt = dt;
+    c.exp_scale = (float)(-1.4426950408889634 / (2.0 * (double)sigma2));
 }
 
 int check_workspace(const void *ws, size_t have, size_t need)
@@ -505,7 +564,7 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     } else {
         if (!X_dev || d < 1 || ld_x < d || !(sigma2 > 0.f)) return RCD_ERR_INVALID_ARG;
         if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
-        return RCD_ERR_UNSUPPORTED;   // recompute sweep: not built yet
+        if (d > (int64_t)0x7fffff00) return RCD_ERR_UNSUPPORTED;
     }
     RCD_TRY(check_workspace(workspace_dev, workspace_bytes,
                             rcd_class_workspace_bytes(n, K, stored ? RCD_MODE_STORED : RCD_MODE_RECOMPUTE)));
@@ -518,8 +577,13 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     c.assign_out = assign_dev;
     c.order_out = order_dev;
     HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
-    hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
-                       (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
+    if (stored) {
+        hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
+                           (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
+    } else {
+        set_recompute_source(c, X_dev, dt, d, ld_x, nullptr, sigma2);
+        RCD_TRY(launch_row_norms(X_dev, dt, n, d, ld_x, nullptr, c.sq, stream));
+    }
     RCD_TRY(run_group(g, stream));
     HIP_TRY(hipMemcpy(obj_host, g.obj_dev, sizeof(double) * K, hipMemcpyDeviceToHost));
     return RCD_OK;
@@ -544,7 +608,6 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
     for (size_t i = 0; i < (size_t)L * K; ++i) obj_host[i] = 0.0;
     if (N == 0) return RCD_OK;
     if (!X_dev || !labels_dev || !assign_dev) return RCD_ERR_INVALID_ARG;
-    if (mode == RCD_MODE_RECOMPUTE) return RCD_ERR_UNSUPPORTED;   // recompute sweep: not built yet
 
     // ---- class split (stable counting sort of indices by label)
     const int nchunks = (int)((N + split::CHUNK - 1) / split::CHUNK);
@@ -584,6 +647,15 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
 
     // ---- classes advance in groups that fit the workspace
     const size_t group_base = cv.off;
+    int max_count = 0;
+    for (int l = 0; l < L; ++l) max_count = std::max(max_count, count[l]);
+    bool stored = mode != RCD_MODE_RECOMPUTE;
+    if (mode == RCD_MODE_AUTO) {
+        // stored if the largest class, alone, fits; else recompute everything
+        const size_t need_one = group_base + group_fixed_bytes(1, K) + class_state_bytes(max_count, K, true) +
+                                up256((size_t)max_count * 4);
+        stored = need_one <= workspace_bytes;
+    }
     int l0 = 0;
     while (l0 < L) {
         // how many consecutive classes fit?
@@ -593,7 +665,7 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
             size_t add = 0;
             int live_next = live;
             if (count[l1] > 0) {
-                add = class_state_bytes(count[l1], K, true) + up256((size_t)count[l1] * 4);
+                add = class_state_bytes(count[l1], K, stored) + (stored ? up256((size_t)count[l1] * 4) : 0);
                 live_next = live + 1;
             }
             if (group_base + group_fixed_bytes(std::max(live_next, 1), K) + need + add > workspace_bytes) break;
@@ -619,14 +691,19 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
             for (int l = l0; l < l1; ++l) {
                 if (count[l] == 0) continue;
                 RcdClass &c = g.host[gi];
-                if (!carve_class(gc, c, count[l], K, cap.data() + (size_t)l * K, true)) return RCD_ERR_WORKSPACE;
-                float *sq = gc.take<float>((size_t)count[l]);
-                if (gc.fail) return RCD_ERR_WORKSPACE;
+                if (!carve_class(gc, c, count[l], K, cap.data() + (size_t)l * K, stored)) return RCD_ERR_WORKSPACE;
                 c.assign_out = assign_dev;
                 c.order_out = order_dev;
                 c.out_index = idx + offset[l];
-                RCD_TRY(launch_similarity(X_dev, dt, count[l], d, ld_x, idx + offset[l], sigma2, c.M, c.ld, c.ld, sq,
-                                          stream));
+                if (stored) {
+                    float *sq = gc.take<float>((size_t)count[l]);
+                    if (gc.fail) return RCD_ERR_WORKSPACE;
+                    RCD_TRY(launch_similarity(X_dev, dt, count[l], d, ld_x, idx + offset[l], sigma2, c.M, c.ld, c.ld,
+                                              sq, stream));
+                } else {
+                    set_recompute_source(c, X_dev, dt, d, ld_x, idx + offset[l], sigma2);
+                    RCD_TRY(launch_row_norms(X_dev, dt, count[l], d, ld_x, idx + offset[l], c.sq, stream));
+                }
                 cls_of[gi++] = l;
             }
             if (g_profile_on) HIP_TRY(hipEventRecord(sim_ev[1], stream));

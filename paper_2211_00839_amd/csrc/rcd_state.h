@@ -8,7 +8,9 @@
 #include <stdint.h>
 
 #define RCD_KMAX 16          // must equal RCD_MAX_K of the public header
-#define RCD_TILE 256         // candidate columns per sweep tile (64 lanes x 4)
+#define RCD_TILE 256         // candidate columns per sweep tile, stored S (64 lanes x 4)
+#define RCD_TILE_RC 128      // candidate columns per sweep tile when S is recomputed
+#define RCD_ROWS_RC 256      // rows of one recomputed tile
 #define RCD_CMAX 32          // most row chunks a class's sweep is split into
 #define RCD_SWEEP_WAVES 8     // waves of a sweep workgroup: each takes an eighth of the chunk's rows
 #define RCD_SWEEP_THREADS (64 * RCD_SWEEP_WAVES)
@@ -22,14 +24,18 @@ struct RcdClass {
     float *part;         // RCD_CMAX x K x ld partial gain sums per row chunk
     float *gain;         // K x ld finished gains, indexed by column position
     int32_t *perm;       // ld: original (class-local) index held by column p
-    int32_t *tilecnt;    // ld/RCD_TILE arrival counters of the sweep's row chunks, per tile
+    int32_t *tilecnt;    // ld/RCD_TILE_RC arrival counters of the sweep's row chunks, per tile
+    float *sq;           // recompute mode: squared norms of the class's rows
     int32_t *assign_out; // caller's arrays (global indexing through out_index)
     int32_t *order_out;  // nullable
     const int32_t *out_index; // nullable: position of local sample v in the caller's arrays
     const void *X;       // recompute mode: features (rows picked through x_index)
     const int32_t *x_index; // nullable
+    int64_t ldx64;
     int32_t n, ld, K, total;    // total = sum of quotas
     int32_t d, ldx, dt, mode;
+    int32_t tw;          // sweep tile width in columns
+    int32_t row_align;   // rows per chunk are a multiple of this
     float exp_scale;     // -log2(e) / (2 sigma^2)
     int32_t target_items;       // sweep workgroups this class should be split into
     // ---- evolving

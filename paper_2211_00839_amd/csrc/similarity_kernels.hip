@@ -12,12 +12,15 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 128;          // tile rows (x_i)
+constexpr int BM = 256;          // tile rows (x_i)
 constexpr int BN = 128;          // tile columns (x_j)
 constexpr int CHUNK = 16;        // bytes per global->LDS chunk
-constexpr int ROWB = 64;         // bytes of k per tile row and k-step
-constexpr int ROWP = 80;         // padded LDS row pitch in bytes (bank spread)
+constexpr int ROWB = 64;         // bytes of k per tile row and stage
+constexpr int ROWP = 80;         // padded LDS row pitch in bytes (spreads the banks)
 constexpr int THREADS = 256;
+constexpr int A_BYTES = BM * ROWP;
+constexpr int B_BYTES = BN * ROWP;
+constexpr int STAGE_BYTES = A_BYTES + B_BYTES;   // 30 KB; two stages per workgroup
 
 template <typename T> struct Elem;
 template <> struct Elem<float> { static constexpr int BK = 16; };
@@ -27,12 +30,15 @@ __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
 
 // One 16-byte chunk of row `row`, k range [k, k + 16/sizeof(T)), zero beyond d.
-template <typename T>
+// FAST: rows are 16-byte aligned and d is a multiple of the stage depth, so every
+// chunk is one aligned vector load and the main loop carries no branches.
+template <typename T, bool FAST>
 __device__ __forceinline__ uint4 load_chunk(const T *__restrict__ X, long long ldx, int row, int k, int d,
                                             bool vec_ok)
 {
     constexpr int E = CHUNK / (int)sizeof(T);
     const T *p = X + (size_t)row * ldx + k;
+    if constexpr (FAST) return *reinterpret_cast<const uint4 *>(p);
     if (vec_ok && k + E <= d) return *reinterpret_cast<const uint4 *>(p);
     union { uint4 u; T e[E]; } tmp;
     tmp.u = make_uint4(0, 0, 0, 0);
@@ -63,17 +69,114 @@ k_row_norms(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ 
     if (lane == 0) sq[i] = (float)a;
 }
 
+// ---------------------------------------------------------------------------
+// Gram main loop of one 256 x 128 tile: acc += X[arow] . X[brow]^T over all of d.
+// 4 waves as 2 x 2; a wave owns 128 x 64 = 4 x 2 MFMA 32x32 tiles (a 4x2 wave
+// tile needs 0.75 KB of LDS reads per MFMA, which the LDS can feed at the full
+// MFMA rate; a 2x2 one cannot).  k advances 64 bytes per row and stage (32 bf16
+// or 16 fp32); stages are double-buffered in LDS, one barrier each: while a
+// stage is multiplied the next one is already in registers on its way to LDS.
+// arow[u], brow[u]: rows of X behind the 16-byte chunks this thread stages.
+// ---------------------------------------------------------------------------
+template <typename T, bool FAST>
+__device__ __forceinline__ void gram_mainloop(const T *__restrict__ X, long long ldx, int d, bool vec_ok,
+                                              const int (&arow)[4], const int (&brow)[2],
+                                              unsigned char *__restrict__ lds, f32x16 (&acc)[4][2])
+{
+    constexpr int BK = Elem<T>::BK;
+    constexpr int EPC = CHUNK / (int)sizeof(T);   // elements per chunk
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int cpart = tid & 3;                    // which 16 bytes of the row's 64
+    const int crow0 = tid >> 2;                   // rows crow0 + 64 u
+
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    uint4 ra[4], rb[2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) ra[u] = load_chunk<T, FAST>(X, ldx, arow[u], cpart * EPC, d, vec_ok);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) rb[u] = load_chunk<T, FAST>(X, ldx, brow[u], cpart * EPC, d, vec_ok);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        *reinterpret_cast<uint4 *>(lds + (crow0 + 64 * u) * ROWP + cpart * CHUNK) = ra[u];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        *reinterpret_cast<uint4 *>(lds + A_BYTES + (crow0 + 64 * u) * ROWP + cpart * CHUNK) = rb[u];
+    __syncthreads();
+
+    // lanes 0-31 take the first 16 bytes of each 32-byte k group, lanes 32-63 the second
+    const int koff = (lane >> 5) * CHUNK;
+    const int a_base = (wr * 128 + (lane & 31)) * ROWP + koff;
+    const int b_base = A_BYTES + (wc * 64 + (lane & 31)) * ROWP + koff;
+
+    int stage = 0;
+    for (int k0 = 0; k0 < d; k0 += BK) {
+        const bool more = k0 + BK < d;
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) ra[u] = load_chunk<T, FAST>(X, ldx, arow[u], k0 + BK + cpart * EPC, d, vec_ok);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) rb[u] = load_chunk<T, FAST>(X, ldx, brow[u], k0 + BK + cpart * EPC, d, vec_ok);
+        }
+        const unsigned char *cur = lds + stage * STAGE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < ROWB / 32; ++kk) {
+            uint4 fa[4], fb[2];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) fa[m] = *reinterpret_cast<const uint4 *>(cur + a_base + m * 32 * ROWP + kk * 32);
+#pragma unroll
+            for (int m = 0; m < 2; ++m) fb[m] = *reinterpret_cast<const uint4 *>(cur + b_base + m * 32 * ROWP + kk * 32);
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, fa[a]), __builtin_bit_cast(bf16x8, fb[b]), acc[a][b], 0, 0, 0);
+            } else {
+                // four 32x32x2 products; lanes<32 carry k = e, lanes>=32 carry k = 4+e,
+                // for both operands alike, so every k of the group is used exactly once
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+#pragma unroll
+                        for (int b = 0; b < 2; ++b) {
+                            const f32x4 va = __builtin_bit_cast(f32x4, fa[a]);
+                            const f32x4 vb = __builtin_bit_cast(f32x4, fb[b]);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], vb[e], acc[a][b], 0, 0, 0);
+                        }
+            }
+        }
+        if (more) {
+            unsigned char *nxt = lds + (stage ^ 1) * STAGE_BYTES;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                *reinterpret_cast<uint4 *>(nxt + (crow0 + 64 * u) * ROWP + cpart * CHUNK) = ra[u];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                *reinterpret_cast<uint4 *>(nxt + A_BYTES + (crow0 + 64 * u) * ROWP + cpart * CHUNK) = rb[u];
+        }
+        __syncthreads();
+        stage ^= 1;
+    }
+}
+
 // Gram tile + Gaussian epilogue.  grid = (column tiles, row tiles).
-// 4 waves in a 2x2 arrangement, each owning a 64x64 block = 2x2 MFMA 32x32 tiles.
-template <typename T>
-__global__ void __launch_bounds__(THREADS)
+template <typename T, bool FAST>
+__global__ void __launch_bounds__(THREADS, 2)
 k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
            const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
            int ncols_pad)
 {
-    constexpr int BK = Elem<T>::BK;
-    __shared__ __attribute__((aligned(16))) unsigned char As[BM * ROWP];
-    __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * ROWP];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -90,94 +193,31 @@ k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ r
     }
 
     const bool vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0) && ((ldx * (long long)sizeof(T)) % 16 == 0);
-
-    // chunk ownership: 128 rows x 4 chunks per operand = 512 chunks, 2 per thread
-    int arow[2], brow[2], crow[2], cpart[2];
+    int arow[4], brow[2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int ai = min(i0 + (tid >> 2) + 64 * u, n - 1);
+        arow[u] = row_index ? row_index[ai] : ai;
+    }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-        const int q = tid + THREADS * u;
-        crow[u] = q >> 2;
-        cpart[u] = q & 3;
-        const int ai = min(i0 + crow[u], n - 1), bj = min(j0 + crow[u], n - 1);
-        arow[u] = row_index ? row_index[ai] : ai;
+        const int bj = min(j0 + (tid >> 2) + 64 * u, n - 1);
         brow[u] = row_index ? row_index[bj] : bj;
     }
 
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    constexpr int EPC = CHUNK / (int)sizeof(T);   // elements per chunk
-    uint4 ra[2], rb[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        ra[u] = load_chunk<T>(X, ldx, arow[u], cpart[u] * EPC, d, vec_ok);
-        rb[u] = load_chunk<T>(X, ldx, brow[u], cpart[u] * EPC, d, vec_ok);
-    }
-
-    for (int k0 = 0; k0 < d; k0 += BK) {
-        __syncthreads();   // previous step's LDS reads are finished
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            *reinterpret_cast<uint4 *>(As + crow[u] * ROWP + cpart[u] * CHUNK) = ra[u];
-            *reinterpret_cast<uint4 *>(Bs + crow[u] * ROWP + cpart[u] * CHUNK) = rb[u];
-        }
-        __syncthreads();
-        if (k0 + BK < d) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                ra[u] = load_chunk<T>(X, ldx, arow[u], k0 + BK + cpart[u] * EPC, d, vec_ok);
-                rb[u] = load_chunk<T>(X, ldx, brow[u], k0 + BK + cpart[u] * EPC, d, vec_ok);
-            }
-        }
-        // lanes 0-31 take the first 16 bytes of each 32-byte k group, lanes 32-63 the second
-        const int koff = (lane >> 5) * CHUNK;
-#pragma unroll
-        for (int kk = 0; kk < ROWB / 32; ++kk) {
-            uint4 fa[2], fb[2];
-#pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                fa[m] = *reinterpret_cast<const uint4 *>(As + (wr * 64 + m * 32 + (lane & 31)) * ROWP + kk * 32 + koff);
-                fb[m] = *reinterpret_cast<const uint4 *>(Bs + (wc * 64 + m * 32 + (lane & 31)) * ROWP + kk * 32 + koff);
-            }
-            if constexpr (sizeof(T) == 2) {
-#pragma unroll
-                for (int a = 0; a < 2; ++a)
-#pragma unroll
-                    for (int b = 0; b < 2; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, fa[a]), __builtin_bit_cast(bf16x8, fb[b]), acc[a][b], 0, 0, 0);
-            } else {
-                // four 32x32x2 products; lanes<32 carry k = e, lanes>=32 carry k = 4+e,
-                // for both operands alike, so every k of the group is used exactly once
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int a = 0; a < 2; ++a)
-#pragma unroll
-                        for (int b = 0; b < 2; ++b) {
-                            const f32x4 va = __builtin_bit_cast(f32x4, fa[a]);
-                            const f32x4 vb = __builtin_bit_cast(f32x4, fb[b]);
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], vb[e], acc[a][b], 0, 0, 0);
-                        }
-            }
-        }
-    }
+    f32x16 acc[4][2];
+    gram_mainloop<T, FAST>(X, ldx, d, vec_ok, arow, brow, lds, acc);
 
     // epilogue: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane>>5) + (r&3)
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    for (int b = 0; b < 2; ++b) {
+        const int j = j0 + wc * 64 + b * 32 + (lane & 31);
+        const float sqj = j < n ? sq[j] : 0.f;
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int j = j0 + wc * 64 + b * 32 + (lane & 31);
-            const float sqj = j < n ? sq[j] : 0.f;
+        for (int a = 0; a < 4; ++a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int i = i0 + wr * 64 + a * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const int i = i0 + wr * 128 + a * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 if (i < n && j < ncols_pad) {
                     float s = 0.f;
                     if (j < n) {

@@ -205,6 +205,39 @@ def test_class_greedy_pitched_input_is_not_modified(rcd):
     check_against_oracle(S, cap, assign.cpu().numpy(), order.cpu().numpy(), obj)
 
 
+# ------------------------------------------------------------------ recompute mode
+@pytest.mark.parametrize("dtype,n,d,r", [("bf16", 700, 256, [1, 1, 2, 2, 3, 3, 4, 8]), ("f32", 515, 64, [1, 2, 3]),
+                                         ("bf16", 300, 40, [2, 1]), ("f32", 130, 24, [1] * 16)])
+def test_class_greedy_recompute_mode(rcd, dtype, n, d, r):
+    """S is never stored: every sweep rebuilds its tiles from X on the matrix cores."""
+    print(f"recompute class greedy {dtype} n={n} d={d} K={len(r)}", flush=True)
+    X = si.make_class(seed=500 + n, n=n, d=d, G=8, dtype=dtype)
+    cap = oracle.quota(n, r)
+    assign, order, obj = rcd.partition_class(X=dev(X), cap=cap, sigma2=float(d))
+    assign, order = assign.cpu().numpy(), order.cpu().numpy()
+    S_ref = oracle.similarity(X, float(d))
+    S_gpu = rcd.similarity(dev(X), float(d)).cpu().numpy()
+    assert rel_err(S_gpu, S_ref) <= (1e-5 if dtype == "f32" else 2e-2)
+    check_against_oracle(S_gpu, cap, assign, order, obj)
+    # the stored-S path on the same class takes the same decisions
+    a2, o2, f2 = rcd.partition_class(S=dev(S_gpu), cap=cap)
+    same = np.mean(a2.cpu().numpy() == assign)
+    print("  recompute vs stored agreement:", same, flush=True)
+    assert np.allclose(f2, obj, rtol=1e-4)
+
+
+def test_dataset_recompute_mode(rcd):
+    ds = si.make_dataset(si.WORKLOADS["large"], L=3, n_c=400, d=128)
+    N = ds.X.shape[0]
+    mn, full = rcd.dataset_workspace_bytes(N, ds.L, 400, len(ds.r), rcd.MODE_RECOMPUTE)
+    _, full_stored = rcd.dataset_workspace_bytes(N, ds.L, 400, len(ds.r), rcd.MODE_STORED)
+    assert full_stored - full >= 3 * 400 * 400 * 4      # no similarity matrix in the workspace
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    assign, order, obj = rcd.partition_dataset(dev(ds.X), dev(ds.labels), ds.L, ds.r, ds.sigma2,
+                                               rcd.MODE_RECOMPUTE, ws)
+    check_dataset(rcd, ds, assign.cpu().numpy(), order.cpu().numpy(), obj)
+
+
 # ------------------------------------------------------------------ data set
 def run_dataset(rcd, ds, L=None, ws_bytes=None):
     L = ds.L if L is None else L
