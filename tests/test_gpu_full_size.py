@@ -1,0 +1,154 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py
+times (rcd_partition_dataset, stored S, all classes advanced together).  The
+oracle cannot replay 50 000 steps of 5000-sample classes in test time, so it
+referees SAMPLED steps: the referee replays the whole GPU trace (cheap state
+updates) and, at the sampled steps, recomputes every candidate's gain from that
+state and checks block and element choice.  Similarity is checked on sampled
+sub-matrices; invariants and objectives are checked in full."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def rcd():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no CPU path")
+    import paper_2211_00839_amd as m
+
+    m.load_library()
+    return m
+
+
+def dev(a):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def sampled_steps(total, rng, k):
+    fixed = list(range(min(6, total))) + [total // 2, total - 2, total - 1]
+    extra = rng.choice(total, size=min(k, total), replace=False).tolist()
+    return sorted(set(s for s in fixed + extra if 0 <= s < total))
+
+
+def run_full(rcd, ds, mode):
+    N = ds.X.shape[0]
+    counts = np.bincount(ds.labels, minlength=ds.L)
+    _, full = rcd.dataset_workspace_bytes(N, ds.L, int(counts.max()), len(ds.r), mode)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    Xd, yd = dev(ds.X), dev(ds.labels)
+    assign, order, obj = rcd.partition_dataset(Xd, yd, ds.L, ds.r, ds.sigma2, mode, ws)
+    del ws
+    return Xd, assign.cpu().numpy(), order.cpu().numpy(), obj
+
+
+def check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps, sim_tol, referee=True):
+    idx = np.flatnonzero(ds.labels == c)
+    n = len(idx)
+    K = len(ds.r)
+    cap = oracle.quota(n, ds.r)
+    a, o = assign[idx], order[idx]
+    # invariants: exact quotas, every sample taken exactly once, class balance
+    assert np.bincount(a, minlength=K).tolist() == cap.tolist()
+    assert np.array_equal(np.sort(o), np.arange(n))
+    if not referee:
+        return None
+    S = rcd.similarity(Xd, ds.sigma2, row_index=dev(idx.astype(np.int32))).cpu().numpy()
+    # similarity on a sampled sub-matrix against the oracle
+    sub = np.sort(rng.choice(n, size=min(192, n), replace=False))
+    ref = oracle.similarity(ds.X[idx[sub]], ds.sigma2)
+    got = S[np.ix_(sub, sub)]
+    assert np.max(np.abs(got - ref) / ref) <= sim_tol
+    # sampled lock step on the same S
+    steps = sampled_steps(n, rng, n_steps)
+    res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, check=steps)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
+    # objectives from the definition
+    for k in range(K):
+        ref_f = oracle.f_value(S, np.flatnonzero(a == k))
+        assert abs(obj[c, k] - ref_f) <= 1e-4 * ref_f
+    return res
+
+
+@pytest.mark.parametrize("name", ["cifar10", "hetero8"])
+def test_full_size_stored_workloads(rcd, name):
+    print(f"full size {name}", flush=True)
+    ds = si.make_dataset(si.WORKLOADS[name])
+    Xd, assign, order, obj = run_full(rcd, ds, rcd.MODE_STORED)
+    stats = rcd.last_stats()
+    assert stats["steps"] == ds.X.shape[0]
+    rng = np.random.default_rng(11)
+    near = 0
+    for c in range(ds.L):
+        # every class: invariants; three classes: similarity samples, referee, objectives
+        res = check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=14, sim_tol=1e-5, referee=c in (0, 4, 9))
+        if res:
+            near += res["near_block"] + res["near_elem"]
+        print(f"  class {c} ok", flush=True)
+    print(f"  sampled near-ties accepted: {near}; stats {stats}", flush=True)
+    # identical class balance in every class
+    per_class = [np.bincount(assign[ds.labels == c], minlength=len(ds.r)) for c in range(ds.L)]
+    assert all(np.array_equal(p, per_class[0]) for p in per_class)
+
+
+def test_full_size_cifar100_every_step(rcd):
+    print("full size cifar100", flush=True)
+    ds = si.make_dataset(si.WORKLOADS["cifar100"])
+    Xd, assign, order, obj = run_full(rcd, ds, rcd.MODE_STORED)
+    rng = np.random.default_rng(12)
+    near = 0
+    for c in range(ds.L):
+        res = check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=500, sim_tol=1e-5, referee=c % 5 == 0)
+        if res:
+            assert res["checked"] == 500            # n_c = 500: every step is refereed
+            near += res["near_block"] + res["near_elem"]
+    print(f"  near-ties accepted over 20 fully refereed classes: {near}", flush=True)
+
+
+def test_large_class_recompute_scaled_every_step(rcd):
+    # same d, dtype, K and capacity ratios as the large-class workload, class size cut so
+    # that the oracle can referee every step; S is never stored (forced recompute)
+    print("large workload scaled to 2 x 2304", flush=True)
+    ds = si.make_dataset(si.WORKLOADS["large"], L=2, n_c=2304)
+    Xd, assign, order, obj = run_full(rcd, ds, rcd.MODE_RECOMPUTE)
+    rng = np.random.default_rng(13)
+    for c in range(ds.L):
+        res = check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=2304, sim_tol=2e-2)
+        assert res["checked"] == 2304
+        print(f"  class {c}: {res}", flush=True)
+
+
+def test_large_class_full_size_window_recompute_equals_stored(rcd):
+    # one class of the large workload at full size (50 000 x 2048 bf16): the first 48
+    # steps (quotas cut to a window, same ratios), once recomputing S inside every sweep
+    # and once streaming a stored S; both must take the same decisions.
+    print("large workload, one full-size class, 48-step window", flush=True)
+    w = si.WORKLOADS["large"]
+    X = si.make_class(seed=w.seed, n=w.n_c, d=w.d, G=w.G, dtype="bf16")
+    Xd = dev(X)
+    cap = np.array([2, 2, 4, 4, 6, 6, 8, 16], dtype=np.int64)
+    a1, o1, f1 = rcd.partition_class(X=Xd, cap=cap, sigma2=float(w.d))
+    s1 = rcd.last_stats()
+    S = rcd.similarity(Xd, float(w.d))
+    a2, o2, f2 = rcd.partition_class(S=S, cap=cap)
+    a1, o1, a2, o2 = a1.cpu().numpy(), o1.cpu().numpy(), a2.cpu().numpy(), o2.cpu().numpy()
+    assert np.bincount(a1[a1 >= 0], minlength=8).tolist() == cap.tolist()
+    assert np.array_equal(a1, a2) and np.array_equal(o1, o2)
+    assert np.allclose(f1, f2, rtol=1e-6)
+    # sampled similarity entries against the oracle, and objective of one block from the definition
+    rng = np.random.default_rng(14)
+    sub = np.sort(rng.choice(w.n_c, size=96, replace=False))
+    ref = oracle.similarity(X[sub], float(w.d))
+    got = S[torch.from_numpy(sub).cuda()][:, torch.from_numpy(sub).cuda()].cpu().numpy()
+    assert np.max(np.abs(got - ref) / ref) <= 2e-2
+    members = np.flatnonzero(a1 == 0)
+    cols = S[:, torch.from_numpy(members).cuda()].max(dim=1).values.double().sum().item()
+    assert abs(f1[0] - cols) <= 1e-4 * cols
+    print(f"  stats {s1}", flush=True)
