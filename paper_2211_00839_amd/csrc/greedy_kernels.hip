@@ -80,15 +80,22 @@ __device__ __forceinline__ const int32_t *plan_prefix(const RcdPlan *plans, int 
     return reinterpret_cast<const int32_t *>(plans + 2) + (size_t)buf * (plans[0].ncls + 1);
 }
 
-// largest c with prefix[c] <= item (prefix is non-decreasing, prefix[ncls] > item)
+// largest c with prefix[c] <= item (prefix is non-decreasing, prefix[ncls] > item).
+// Up to 64 classes at a time: lane c reads prefix[c] and a ballot counts, one trip
+// to memory instead of a chain of dependent ones.
 __device__ __forceinline__ int find_class(const int32_t *prefix, int ncls, int item)
 {
-    int lo = 0, hi = ncls;
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (prefix[mid] <= item) lo = mid; else hi = mid;
+    const int lane = threadIdx.x & 63;
+    int c = 0;
+    for (int base = 0; base < ncls; base += 64) {
+        const int i = base + lane;
+        const bool le = i < ncls && prefix[i] <= item;
+        const int cnt = __popcll(__ballot(le));
+        if (cnt == 0) break;
+        c = base + cnt - 1;
+        if (cnt < 64) break;
     }
-    return lo;
+    return __builtin_amdgcn_readfirstlane(c);
 }
 
 // ---------------------------------------------------------------------------
@@ -231,7 +238,9 @@ __device__ __forceinline__ int effective_pos(const StepShared &sh, int npatch, i
 // are applied by rcd_k_apply, which has the whole GPU for the strided column
 // traffic.  A block is stepped at most once per call (its gains go stale), so
 // a call takes at most K steps.
-template <int NT>
+// SCOPED: the gains were written earlier in this same launch by other workgroups
+// (fused round), so they are read at device scope; in its own launch plain loads do.
+template <int NT, bool SCOPED>
 __device__ __forceinline__ void class_steps(RcdClass &st, StepShared &sh)
 {
     const int tid = threadIdx.x;
@@ -280,20 +289,21 @@ __device__ __forceinline__ void class_steps(RcdClass &st, StepShared &sh)
         const int npatch = sh.npatch;
         unsigned long long best = 0ull;
         int bpos = -1;
-        for (int p0 = 0; p0 < nR; p0 += 8 * NT) {
-            float gv[8];
-            int pv[8];
+        constexpr int UA = NT >= 1024 ? 8 : 12;   // loads in flight per thread and array
+        for (int p0 = 0; p0 < nR; p0 += UA * NT) {
+            float gv[UA];
+            int pv[UA];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < UA; ++u) {
                 const int p = p0 + u * NT + tid;
                 if (p < nR) {
                     const int e = npatch ? effective_pos(sh, npatch, p) : p;
-                    gv[u] = dev_load(g + e);
+                    gv[u] = SCOPED ? dev_load(g + e) : g[e];
                     pv[u] = perm[e];
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < UA; ++u) {
                 const int p = p0 + u * NT + tid;
                 if (p < nR) {
                     const unsigned long long key = pack_key(gv[u], pv[u]);
@@ -390,39 +400,70 @@ __device__ __forceinline__ void class_steps(RcdClass &st, StepShared &sh)
 }
 
 // Lay out the next round's sweep over all classes into plan buffer `next` and
-// retire buffer `cur_buf`.  Called by exactly one thread, after the last arrival.
-__device__ __forceinline__ void write_plan(RcdClass *classes, RcdPlan *plans, int cur_buf, int next)
+// retire buffer `cur_buf`.  Called by every thread of one workgroup (NT threads)
+// after the last arrival: thread c reads class c's published state, a block scan
+// turns the per-class workgroup counts into the prefix array.  scratch: NT/64 ints of LDS.
+template <int NT>
+__device__ __forceinline__ void write_plan(RcdClass *classes, RcdPlan *plans, int cur_buf, int next, int *scratch)
 {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ncls = plans[0].ncls;
     int32_t *ip = plan_prefix(plans, next);
     int items = 0, ndone = 0, nactive = 0;
-    for (int c = 0; c < ncls; ++c) {
-        const RcdClass &o = classes[c];
-        const int nneed = dev_load((gci32)&o.nneed);
-        ip[c] = items;
-        if (nneed > 0) {
-            const int tiles = (dev_load((gci32)&o.nR) + o.tw - 1) / o.tw;
-            items += tiles * dev_load((gci32)&o.C);
-            nactive += 1;
+    for (int base = 0; base < ncls; base += NT) {
+        const int c = base + tid;
+        int it = 0, dn = 0, ac = 0;
+        if (c < ncls) {
+            const RcdClass &o = classes[c];
+            const int nneed = dev_load((gci32)&o.nneed);
+            const int nR = dev_load((gci32)&o.nR);
+            const int C = dev_load((gci32)&o.C);
+            dn = dev_load((gci32)&o.done) ? 1 : 0;
+            if (nneed > 0) {
+                it = ((nR + o.tw - 1) / o.tw) * C;
+                ac = 1;
+            }
         }
-        ndone += dev_load((gci32)&o.done) ? 1 : 0;
+        int incl = it;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_up(incl, off);
+            if (lane >= off) incl += v;
+        }
+        __syncthreads();
+        if (lane == 63) scratch[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) {
+            const int v = scratch[w];
+            if (w < wave) before += v;
+            total += v;
+        }
+        if (c < ncls) ip[c] = items + before + incl - it;
+        items += total;
+        ndone += __syncthreads_count(dn);
+        nactive += __syncthreads_count(ac);
     }
-    ip[ncls] = items;
-    plans[next].items = items;
-    plans[next].nactive = nactive;
-    plans[next].ndone = ndone;
-    plans[next].arrive = 0;
-    if (cur_buf >= 0) {
-        // late workgroups of this launch only ever see "nothing to do" here
-        plans[cur_buf].items = 0;
-        plans[cur_buf].nactive = 0;
-        plans[cur_buf].ndone = ndone;
+    if (tid == 0) {
+        ip[ncls] = items;
+        plans[next].items = items;
+        plans[next].nactive = nactive;
+        plans[next].ndone = ndone;
+        plans[next].arrive = 0;
+        if (cur_buf >= 0) {
+            // late workgroups of this launch only ever see "nothing to do" here
+            plans[cur_buf].items = 0;
+            plans[cur_buf].nactive = 0;
+            plans[cur_buf].ndone = ndone;
+        }
     }
 }
 
 // What follows a workgroup's sweep item (steps 2-4 of a round, see rcd_k_round).
 // NT threads in the workgroup, TW columns per tile.
-template <int NT, int TW>
+// FUSE = false stops after step 2: the step loops then run in their own launch (rcd_k_steps).
+template <int NT, int TW, bool FUSE>
 __device__ __forceinline__ void round_tail(RcdClass &st, RcdClass *classes, RcdPlan *plans, int buf, int tile,
                                            int tiles, StepShared &sh, int *s_flag)
 {
@@ -453,13 +494,14 @@ __device__ __forceinline__ void round_tail(RcdClass &st, RcdClass *classes, RcdP
         }
         if (tid == 0) st.tilecnt[tile] = 0;
     }
+    if constexpr (!FUSE) return;
     // ---- 3. last tile of this class?  then run the class's greedy steps
     if (!arrive_last(&st.tiles_done, tiles, s_flag)) return;
     if (tid == 0) st.tiles_done = 0;
-    class_steps<NT>(st, sh);
+    class_steps<NT, true>(st, sh);
     // ---- 4. last active class of the group?  then lay out the next round
-    if (arrive_last(&plans[buf].arrive, plans[buf].nactive, s_flag) && tid == 0)
-        write_plan(classes, plans, buf, buf ^ 1);
+    if (arrive_last(&plans[buf].arrive, plans[buf].nactive, s_flag))
+        write_plan<NT>(classes, plans, buf, buf ^ 1, reinterpret_cast<int *>(sh.wkey));
 }
 
 } // namespace
@@ -471,14 +513,17 @@ rcd_k_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
 {
     __shared__ StepShared sh;
     __shared__ int s_flag;
-    class_steps<RCD_STEP_THREADS>(classes[blockIdx.x], sh);
-    if (arrive_last(&plans[1].arrive, (int)gridDim.x, &s_flag) && threadIdx.x == 0) {
-        plans[1].arrive = 0;
-        write_plan(classes, plans, -1, 0);
+    class_steps<RCD_STEP_THREADS, false>(classes[blockIdx.x], sh);
+    if (arrive_last(&plans[1].arrive, (int)gridDim.x, &s_flag)) {
+        if (threadIdx.x == 0) plans[1].arrive = 0;
+        write_plan<RCD_STEP_THREADS>(classes, plans, -1, 0, reinterpret_cast<int *>(sh.wkey));
     }
 }
 
-// One round for every class of the group, in a single launch:
+// One round for every class of the group, in a single launch (FUSE), or its
+// first two parts (the host then launches rcd_k_steps for parts 3 and 4: with
+// many classes in flight the sweep is bandwidth-bound and the step loop of the
+// class that finishes last would only lengthen it):
 //   1. sweep: every workgroup computes one (class, tile, row chunk) of partial gains
 //   2. the workgroup that completes a tile adds its chunks in order -> gain
 //   3. the workgroup that completes a class runs that class's greedy steps
@@ -486,7 +531,11 @@ rcd_k_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
 //   4. the workgroup that completes the last class writes the next round's plan
 // Completion is detected with arrival counters; nothing ever waits.  Launch r reads plan buffer r&1 and writes
 // the other one.
-extern "C" __global__ void __launch_bounds__(RCD_SWEEP_THREADS)
+// KCAP: no class of the group has more blocks than this (the host picks the
+// smallest instance that fits, which keeps the register count, hence the
+// occupancy, of small-K data sets independent of the K = 16 code).
+template <int KCAP, bool FUSE>
+__global__ void __launch_bounds__(RCD_SWEEP_THREADS)
 rcd_k_round(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int buf)
 {
     __shared__ float4 lds[RCD_SWEEP_WAVES * 4 * 64];
@@ -507,13 +556,13 @@ rcd_k_round(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int buf
     if (nneed <= 1) sweep_body<1>(st, tile, chunk, lds);
     else if (nneed == 2) sweep_body<2>(st, tile, chunk, lds);
     else if (nneed == 3) sweep_body<3>(st, tile, chunk, lds);
-    else if (nneed == 4) sweep_body<4>(st, tile, chunk, lds);
+    else if (nneed == 4 || KCAP <= 4) sweep_body<4>(st, tile, chunk, lds);
     else if (nneed <= 6) sweep_body<6>(st, tile, chunk, lds);
-    else if (nneed <= 8) sweep_body<8>(st, tile, chunk, lds);
+    else if (nneed <= 8 || KCAP <= 8) sweep_body<8>(st, tile, chunk, lds);
     else if (nneed <= 12) sweep_body<12>(st, tile, chunk, lds);
     else sweep_body<16>(st, tile, chunk, lds);
 
-    round_tail<RCD_SWEEP_THREADS, RCD_TILE>(st, classes, plans, buf, tile, tiles, sh, &s_flag);
+    round_tail<RCD_SWEEP_THREADS, RCD_TILE, FUSE>(st, classes, plans, buf, tile, tiles, sh, &s_flag);
 }
 
 // Applies what the step loops of the last round decided.  grid = (row blocks, ncls),

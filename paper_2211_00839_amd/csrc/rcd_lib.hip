@@ -191,17 +191,25 @@ int run_group(Group &g, hipStream_t stream)
     const int esz = first.dt == RCD_F32 ? 4 : 2;
     const bool fast = recompute && (reinterpret_cast<uintptr_t>(first.X) & 15) == 0 &&
                       ((first.ldx64 * esz) % 16) == 0 && ((int64_t)first.d * esz) % sim::ROWB == 0;
+    // One launch per round (sweep + step loops fused) pays off when few classes are in
+    // flight; with many, the sweep is bandwidth-bound and the step loops get their own launch.
+    const bool fused = env_int("RCD_FUSED", ncls <= 2 ? 1 : 0, 0, 1) != 0;
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
     void (*apply_rc)(RcdClass *, int) = nullptr;
     if (recompute) {
         if (first.dt == RCD_F32) {
-            round_rc = fast ? rcd_k_round_rc<float, true> : rcd_k_round_rc<float, false>;
+            round_rc = fused ? (fast ? rcd_k_round_rc<float, true, true> : rcd_k_round_rc<float, false, true>)
+                             : (fast ? rcd_k_round_rc<float, true, false> : rcd_k_round_rc<float, false, false>);
             apply_rc = rcd_k_apply_rc<float>;
         } else {
-            round_rc = fast ? rcd_k_round_rc<__bf16, true> : rcd_k_round_rc<__bf16, false>;
+            round_rc = fused ? (fast ? rcd_k_round_rc<__bf16, true, true> : rcd_k_round_rc<__bf16, false, true>)
+                             : (fast ? rcd_k_round_rc<__bf16, true, false> : rcd_k_round_rc<__bf16, false, false>);
             apply_rc = rcd_k_apply_rc<__bf16>;
         }
     }
+    void (*round_st)(RcdClass *, RcdPlan *, int) =
+        fused ? (g.K <= 4 ? rcd_k_round<4, true> : (g.K <= 8 ? rcd_k_round<8, true> : rcd_k_round<16, true>))
+              : (g.K <= 4 ? rcd_k_round<4, false> : (g.K <= 8 ? rcd_k_round<8, false> : rcd_k_round<16, false>));
     const dim3 apply_rc_grid((unsigned)((max_n + 3) / 4), (unsigned)ncls);
     auto launch_apply = [&](int rn) {
         if (recompute) hipLaunchKernelGGL(apply_rc, apply_rc_grid, dim3(256), 0, stream, g.classes_dev, rn);
@@ -214,7 +222,7 @@ int run_group(Group &g, hipStream_t stream)
     const bool prof = g_profile_on != 0;
     if (prof) {
         for (int s = 0; s < 2; ++s)
-            while ((int)g_prof_ev[s].size() < 2 * rounds + 1) {
+            while ((int)g_prof_ev[s].size() < 3 * rounds + 1) {
                 hipEvent_t e;
                 HIP_TRY(hipEventCreate(&e));
                 g_prof_ev[s].push_back(e);
@@ -226,8 +234,9 @@ int run_group(Group &g, hipStream_t stream)
         std::vector<hipEvent_t> &e = g_prof_ev[batch & 1];
         for (int r = 0; r < rounds; ++r) {
             float ms = 0.f;
-            if (hipEventElapsedTime(&ms, e[2 * r], e[2 * r + 1]) == hipSuccess) g_prof[1] += ms;
-            if (hipEventElapsedTime(&ms, e[2 * r + 1], e[2 * r + 2]) == hipSuccess) g_prof[0] += ms;
+            if (hipEventElapsedTime(&ms, e[3 * r], e[3 * r + 1]) == hipSuccess) g_prof[1] += ms;
+            if (hipEventElapsedTime(&ms, e[3 * r + 1], e[3 * r + 2]) == hipSuccess) g_prof[0] += ms;
+            if (hipEventElapsedTime(&ms, e[3 * r + 2], e[3 * r + 3]) == hipSuccess) g_prof[2] += ms;
         }
         g_prof[3] += rounds;
     };
@@ -245,18 +254,22 @@ int run_group(Group &g, hipStream_t stream)
         std::vector<hipEvent_t> *pe = prof ? &g_prof_ev[b & 1] : nullptr;
         if (pe) (void)hipEventRecord((*pe)[0], stream);
         for (int r = 0; r < rounds; ++r) {
+            const int buf = fused ? (round_no & 1) : 0;
             if (recompute)
-                hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), 0, stream, g.classes_dev, g.plan_dev,
-                                   round_no & 1);
+                hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), 0, stream, g.classes_dev, g.plan_dev, buf);
             else
-                hipLaunchKernelGGL(rcd_k_round, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
-                                   g.plan_dev, round_no & 1);
+                hipLaunchKernelGGL(round_st, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
+                                   g.plan_dev, buf);
             ++round_no;
-            if (pe) (void)hipEventRecord((*pe)[2 * r + 1], stream);
+            if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
+            if (!fused)
+                hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev,
+                                   g.plan_dev);
+            if (pe) (void)hipEventRecord((*pe)[3 * r + 2], stream);
             launch_apply(round_no + 1);
-            if (pe) (void)hipEventRecord((*pe)[2 * r + 2], stream);
+            if (pe) (void)hipEventRecord((*pe)[3 * r + 3], stream);
         }
-        launches += 2 * (int64_t)rounds;
+        launches += (fused ? 2 : 3) * (int64_t)rounds;
         hipError_t le = hipGetLastError();
         if (le != hipSuccess) {
             snprintf(g_hip_err, sizeof g_hip_err, "kernel launch -> %s", hipGetErrorString(le));
@@ -527,7 +540,10 @@ int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const flo
                        (const RcdClass *)g.classes_dev, cur_dev);
     HIP_TRY(hipMemsetAsync(c.tilecnt, 0, (size_t)(c.ld / RCD_TILE) * 4, stream));
     // total = 0: after the sweep the class's step loop finds nothing to do
-    hipLaunchKernelGGL(rcd_k_round, dim3(plan.p[0].items), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
+    void (*sweep_kernel)(RcdClass *, RcdPlan *, int) = rcd_k_round<16, true>;
+    if (K <= 4) sweep_kernel = rcd_k_round<4, true>;
+    else if (K <= 8) sweep_kernel = rcd_k_round<8, true>;
+    hipLaunchKernelGGL(sweep_kernel, dim3(plan.p[0].items), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
                        g.plan_dev, 0);
     hipLaunchKernelGGL(rcd_k_export_gains, dim3((unsigned)((n + 255) / 256), K), dim3(256), 0, stream,
                        (const RcdClass *)g.classes_dev, gains_dev);

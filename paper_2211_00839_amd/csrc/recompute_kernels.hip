@@ -33,11 +33,25 @@ __device__ __forceinline__ void recompute_body(const RcdClass &st, int tile, int
 
     // candidates of this tile: B operand rows, and for the epilogue the sample and norm of my two columns
     int brow[2];
+    const T *gp[6];            // FAST: this lane's six chunk addresses of a stage (A part refreshed per row tile)
+    int a_trow[6], a_chunk[6];
+    if constexpr (FAST) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        int v = perm[tile * RCD_TILE_RC + (tid >> 2) + 64 * u];
-        v = min(max(v, 0), n - 1);
-        brow[u] = xi ? xi[v] : v;
+        for (int u = 0; u < 6; ++u) {
+            dma_slot(wave, u, lane, &a_trow[u], &a_chunk[u]);
+            if (a_trow[u] >= BM) {
+                int v = perm[tile * RCD_TILE_RC + a_trow[u] - BM];
+                v = min(max(v, 0), n - 1);
+                gp[u] = X + (size_t)(xi ? xi[v] : v) * ldx + a_chunk[u] * (CHUNK / (int)sizeof(T));
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            int v = perm[tile * RCD_TILE_RC + (tid >> 2) + 64 * u];
+            v = min(max(v, 0), n - 1);
+            brow[u] = xi ? xi[v] : v;
+        }
     }
     int vcol[2];
     float sqv[2];
@@ -46,9 +60,10 @@ __device__ __forceinline__ void recompute_body(const RcdClass &st, int tile, int
         int v = perm[tile * RCD_TILE_RC + wc * 64 + b * 32 + (lane & 31)];
         v = min(max(v, 0), n - 1);
         vcol[b] = v;
-        sqv[b] = sq[v];
+        sqv[b] = sq[v] * st.exp_scale;
     }
     const float exp_scale = st.exp_scale;
+    const float scale2 = -2.f * exp_scale;
 
     float gsum[KS][2];
 #pragma unroll
@@ -57,24 +72,41 @@ __device__ __forceinline__ void recompute_body(const RcdClass &st, int tile, int
     const int row_begin = chunk * st.rpc;
     const int row_end = min(n, row_begin + st.rpc);
     for (int i0 = row_begin; i0 < row_end; i0 += RCD_ROWS_RC) {
-        // stage coverage values and norms of the 256 rows (rows past n: +inf coverage = no gain)
-        __syncthreads();
-        {
+        // coverage values and norms of the 256 rows (rows past n: +inf coverage = no gain).
+        // In the fast path they are staged after the main loop, in the LDS it has freed.
+        auto stage_rows = [&]() {
             const int i = i0 + tid;
-            sq_s[tid] = i < n ? sq[i] : 0.f;
+            sq_s[tid] = i < n ? sq[i] * exp_scale : 0.f;
 #pragma unroll
             for (int k = 0; k < KS; ++k)
                 cur_s[k * RCD_ROWS_RC + tid] = i < n ? ((gcf32)st.cur)[(size_t)kb[k] * ld + i] : __builtin_inff();
-        }
-        int arow[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int ai = min(i0 + (tid >> 2) + 64 * u, n - 1);
-            arow[u] = xi ? xi[ai] : ai;
-        }
+        };
         f32x16 acc[4][2];
-        gram_mainloop<T, FAST>(X, ldx, d, vec_ok, arow, brow, lds, acc);   // ends with a barrier
+        __syncthreads();       // the previous tile's epilogue is done with cur_s / sq_s
+        if constexpr (FAST) {
+#pragma unroll
+            for (int u = 0; u < 6; ++u)
+                if (a_trow[u] < BM) {
+                    const int ai = min(i0 + a_trow[u], n - 1);
+                    gp[u] = X + (size_t)(xi ? xi[ai] : ai) * ldx + a_chunk[u] * (CHUNK / (int)sizeof(T));
+                }
+            gram_mainloop_dma<T>(gp, d, lds, acc);   // ends with a barrier: the ring is free
+            stage_rows();
+            __syncthreads();
+        } else {
+            stage_rows();
+            int arow[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ai = min(i0 + (tid >> 2) + 64 * u, n - 1);
+                arow[u] = xi ? xi[ai] : ai;
+            }
+            gram_mainloop<T, false>(X, ldx, d, vec_ok, arow, brow, lds, acc);   // ends with a barrier
+        }
 
+        // does any candidate of this tile sit among these 256 rows?  (its own similarity is exactly 1)
+        const bool maybe_diag = __any((vcol[0] >= i0 && vcol[0] < i0 + RCD_ROWS_RC) ||
+                                      (vcol[1] >= i0 && vcol[1] < i0 + RCD_ROWS_RC));
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
 #pragma unroll
@@ -87,9 +119,8 @@ __device__ __forceinline__ void recompute_body(const RcdClass &st, int tile, int
                     const float q[4] = {sqi.x, sqi.y, sqi.z, sqi.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        float dist = q[e] + sqv[b] - 2.f * acc[a][b][rq * 4 + e];
-                        dist = fmaxf(dist, 0.f);
-                        s[b][e] = (i0 + rl + e == vcol[b]) ? 1.f : exp2f(dist * exp_scale);
+                        s[b][e] = rbf_value(acc[a][b][rq * 4 + e], q[e], sqv[b], scale2);
+                        if (maybe_diag && i0 + rl + e == vcol[b]) s[b][e] = 1.f;
                     }
                 }
 #pragma unroll
@@ -136,13 +167,16 @@ __device__ __forceinline__ void recompute_body(const RcdClass &st, int tile, int
 
 } // namespace
 
-template <typename T, bool FAST>
+template <typename T, bool FAST, bool FUSE>
 __global__ void __launch_bounds__(256, 2)
 rcd_k_round_rc(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int buf)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * sim::STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) float cur_s[RCD_KMAX * RCD_ROWS_RC];
-    __shared__ __attribute__((aligned(16))) float sq_s[RCD_ROWS_RC];
+    // fast path: the coverage/norm staging area aliases the start of the (then idle) stage ring
+    constexpr int ROWS_BYTES = (RCD_KMAX + 1) * RCD_ROWS_RC * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[FAST ? sim::DMA_LDS_BYTES : 2 * sim::STAGE_BYTES + ROWS_BYTES];
+    float *cur_s = reinterpret_cast<float *>(FAST ? lds : lds + 2 * sim::STAGE_BYTES);
+    float *sq_s = cur_s + RCD_KMAX * RCD_ROWS_RC;
+    static_assert(ROWS_BYTES <= sim::DMA_LDS_BYTES, "row staging area must fit in the stage ring");
     __shared__ StepShared sh;
     __shared__ int s_flag;
     const RcdPlan *plan = plans + buf;
@@ -162,7 +196,7 @@ rcd_k_round_rc(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
     else if (nneed <= 4) recompute_body<T, FAST, 4>(st, tile, chunk, lds, cur_s, sq_s);
     else if (nneed <= 8) recompute_body<T, FAST, 8>(st, tile, chunk, lds, cur_s, sq_s);
     else recompute_body<T, FAST, 16>(st, tile, chunk, lds, cur_s, sq_s);
-    round_tail<256, RCD_TILE_RC>(st, classes, plans, buf, tile, tiles, sh, &s_flag);
+    round_tail<256, RCD_TILE_RC, FUSE>(st, classes, plans, buf, tile, tiles, sh, &s_flag);
 }
 
 // Apply kernel of the recompute mode: there is no stored matrix, so the coverage
@@ -191,9 +225,9 @@ rcd_k_apply_rc(RcdClass *__restrict__ classes, int round_no)
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
             if (lane == 0) {
-                float dist = st.sq[j] + st.sq[v] - 2.f * dot;
-                dist = fmaxf(dist, 0.f);
-                const float s = (j == v) ? 1.f : exp2f(dist * st.exp_scale);
+                const float s = (j == v) ? 1.f
+                                         : sim::rbf_value(dot, st.sq[j] * st.exp_scale, st.sq[v] * st.exp_scale,
+                                                          -2.f * st.exp_scale);
                 float *c = st.cur + (size_t)st.ujs[i] * ld + j;
                 if (s > *c) *c = s;
             }
