@@ -70,6 +70,56 @@ def cpu_baseline(ds, budget_steps):
     }
 
 
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def extra_kernels(rcd, si, torch):
+    """The two matrix-core kernels at the shape of one class of the large-class workload
+    (50 000 x 2048 bf16, K = 8): the similarity build, and the first rounds of a greedy run
+    that recomputes S inside every sweep.  Timed with events on the stream they run on."""
+    w = si.WORKLOADS["large"]
+    n, d = w.n_c, w.d
+    X = si.make_class(seed=w.seed, n=n, d=d, G=w.G, dtype="bf16")
+    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.bfloat16)
+    res = {}
+    S = torch.empty((n, n), dtype=torch.float32, device="cuda")
+    ws = torch.empty(n * 4 + 256, dtype=torch.uint8, device="cuda")
+    rcd.similarity(Xd, float(d), out=S, workspace=ws)
+    reps = 3
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        rcd.similarity(Xd, float(d), out=S, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    tf = 2.0 * n * n * d / (ms * 1e-3) / 1e12
+    res["similarity_large_class"] = {
+        "kernel": "sim::k_gram_rbf<bf16> (+ row norms)", "shape": f"n={n} d={d} bf16 -> fp32 S", "ms": ms,
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                     "frac": tf / MFMA_PEAK_TFLOPS["bf16"],
+                     "flops": "2 n^2 d, every tile computed (symmetry not exploited)"}}
+    del S
+    # recompute mode: quotas cut to a 48-step window (same ratios), S never stored
+    cap = np.array([2, 2, 4, 4, 6, 6, 8, 16], dtype=np.int64)
+    rcd.profile(True)
+    rcd.partition_class(X=Xd, cap=cap, sigma2=float(d))
+    prof = rcd.profile_read()
+    st = rcd.last_stats()
+    rcd.profile(False)
+    flops = 2.0 * st["entries_streamed"] * d
+    tf = flops / (prof["sweep_ms"] * 1e-3) / 1e12 if prof["sweep_ms"] > 0 else 0.0
+    res["recompute_sweep_large_class"] = {
+        "kernel": "rcd_k_round_rc<bf16> (S tiles rebuilt by MFMA inside the gain sweep)",
+        "shape": f"n={n} d={d} bf16, K=8, first {st['steps']} greedy steps, {st['sweeps']} sweeps",
+        "sweep_ms_total": prof["sweep_ms"], "steps_ms_total": prof["steps_ms"], "apply_ms_total": prof["apply_ms"],
+        "useful_evals_per_s": st["useful_evals"] / ((prof["sweep_ms"] + prof["steps_ms"] + prof["apply_ms"]) * 1e-3),
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                     "frac": tf / MFMA_PEAK_TFLOPS["bf16"], "flops": "2 |R| n d per sweep"}}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +127,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cifar10")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the large-class similarity / recompute-sweep lines")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy (known traffic) so that rocprofv3 byte counters can be scaled")
     ap.add_argument("--scale", default="", help="L,n_c,d override for quick runs (not a valid bench line)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -93,6 +146,14 @@ def main():
         sys.exit(2)
     rcd.load_library()
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "4 device copies of 1 GiB: each reads 2^30 B and writes 2^30 B"}))
+        return
 
     w = si.WORKLOADS[args.workload]
     kw = {}
@@ -138,7 +199,7 @@ def main():
     sweep_bytes = 4.0 * pstats["entries_streamed"]
     achieved = sweep_bytes / (prof["sweep_ms"] * 1e-3) / 1e9 if prof["sweep_ms"] > 0 else 0.0
     roofline = {
-        "kernel": "rcd_k_sweep",
+        "kernel": "rcd_k_round (gain sweep of all stale blocks + chunk finalisation)",
         "bound": "hbm",
         "achieved": achieved,
         "peak": HBM_PEAK_GBS,
@@ -176,10 +237,12 @@ def main():
         "greedy_steps": stats["steps"],
         "sweeps": stats["sweeps"],
         "kernel_launches": stats["launches"],
-        "time_split_ms": {"similarity": prof["similarity_ms"], "steps": prof["steps_ms"], "sweep": prof["sweep_ms"],
-                          "instrumented_step_total": prof_ms},
+        "time_split_ms": {"similarity": prof["similarity_ms"], "sweep": prof["sweep_ms"], "steps": prof["steps_ms"],
+                          "apply": prof["apply_ms"], "instrumented_step_total": prof_ms},
         "roofline": roofline,
     }
+    if not args.scale and not args.no_extra:
+        out["extra"] = extra_kernels(rcd, si, torch)
     if not args.no_cpu_baseline:
         n0 = int(counts[0])
         out["cpu_baseline"] = cpu_baseline(ds, budget_steps=min(96, n0))

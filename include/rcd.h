@@ -155,9 +155,10 @@ void rcd_last_stats(int64_t *out8_host);
  * later partition calls put HIP events between the launches of every round
  * (on the caller's stream) and add up the elapsed times; rcd_profile(0) turns
  * it off; either call clears the sums.  rcd_profile_read: out[0] = ms spent in
- * the steps launches, out[1] = ms in the gain-sweep launches, out[2] = 0,
- * out[3] = rounds timed (each launches the two kernels once), out[4] = ms of
- * the similarity builds of rcd_partition_dataset, out[5..7] = 0.
+ * the step-loop launches (0 when the step loops run fused into the sweep launch),
+ * out[1] = ms in the gain-sweep launches, out[2] = ms in the apply launches,
+ * out[3] = rounds timed, out[4] = ms of the similarity builds of
+ * rcd_partition_dataset, out[5..7] = 0.
  */
 void rcd_profile(int enable);
 void rcd_profile_read(double *out8_host);

@@ -236,4 +236,4 @@ def profile(enable: bool) -> None:
 def profile_read() -> dict:
     out = np.zeros(8, dtype=np.float64)
     load_library().rcd_profile_read(_np_ptr(out))
-    return dict(steps_ms=out[0], sweep_ms=out[1], rounds=int(out[3]), similarity_ms=out[4])
+    return dict(steps_ms=out[0], sweep_ms=out[1], apply_ms=out[2], rounds=int(out[3]), similarity_ms=out[4])

@@ -40,6 +40,13 @@ __device__ __forceinline__ void dev_store(int32_t RCD_GLOBAL *p, int32_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// 16-byte device-scope store (one write-through transaction instead of four partial ones)
+__device__ __forceinline__ void dev_store4(float RCD_GLOBAL *p, float x, float y, float z, float w)
+{
+    typedef float v4 __attribute__((ext_vector_type(4)));
+    const v4 v = {x, y, z, w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
 __device__ __forceinline__ float dev_load(const float RCD_GLOBAL *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -118,7 +125,10 @@ __device__ __forceinline__ void sweep_body(const RcdClass &st, int tile, int chu
     const int row1 = min(st.n, row0 + rpw);
     const int nneed = st.nneed;
 
-    const gcf32 Mp = (gcf32)st.M + (size_t)tile * RCD_TILE + lane * 4;
+    // lanes whose four columns are all dead (past the last live candidate) re-read column 0
+    // instead: one shared line per row rather than a wasted fetch of their own
+    const int col0 = tile * RCD_TILE + lane * 4;
+    const gcf32 Mp = (gcf32)st.M + (col0 < st.nR ? col0 : 0);
     ccf32 cp[KS];
     int kb[KS];
 #pragma unroll
@@ -181,8 +191,7 @@ __device__ __forceinline__ void sweep_body(const RcdClass &st, int tile, int chu
             for (int i = 0; i < KS; ++i)
                 if (i == mine) kmine = kb[i];
             const gf32 dst = part + (size_t)kmine * ld;
-            dev_store(dst + 0, a.x); dev_store(dst + 1, a.y);
-            dev_store(dst + 2, a.z); dev_store(dst + 3, a.w);
+            dev_store4(dst, a.x, a.y, a.z, a.w);
         }
         __syncthreads();
     }

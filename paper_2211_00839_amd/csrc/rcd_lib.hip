@@ -25,7 +25,7 @@ thread_local int64_t g_stats[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 thread_local RcdPlan *g_pinned = nullptr;   // 2 progress slots of 2 plan headers, pinned, never freed
 // optional per-kernel timing (HIP events between the launches of a round)
 thread_local int g_profile_on = 0;
-thread_local double g_prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // ms: steps, sweep, -, rounds, similarity ms
+thread_local double g_prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // ms: steps, sweep, apply; rounds; similarity ms
 thread_local std::vector<hipEvent_t> g_prof_ev[2];
 
 #define HIP_TRY(expr)                                                                      \
