@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <vector>
+#include <thread>
 
 #include "../../include/rcd.h"
 #include "rcd_state.h"
@@ -22,11 +23,12 @@ namespace {
 
 thread_local char g_hip_err[320] = "";
 thread_local int64_t g_stats[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-thread_local RcdPlan *g_pinned = nullptr;   // 2 progress slots of 2 plan headers, pinned, never freed
+thread_local RcdPlan *g_pinned = nullptr;   // per lane 2 progress slots of 2 plan headers, pinned, never freed
 // optional per-kernel timing (HIP events between the launches of a round)
 thread_local int g_profile_on = 0;
 thread_local double g_prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // ms: steps, sweep, apply; rounds; similarity ms
-thread_local std::vector<hipEvent_t> g_prof_ev[2];
+thread_local std::vector<hipEvent_t> g_prof_ev[4];
+thread_local hipStream_t g_side[4] = {nullptr, nullptr, nullptr, nullptr};   // created on first use, never destroyed
 
 #define HIP_TRY(expr)                                                                      \
     do {                                                                                   \
@@ -85,15 +87,23 @@ size_t class_state_bytes(int64_t n, int K, bool stored)
     return b;
 }
 
+// Classes of a group may be dealt to this many lanes that advance side by side.
+constexpr int RCD_MAX_LANES = 4;
+// Progress records (and their events) a lane cycles through: batches in flight + 1 at most.
+constexpr int RCD_SLOTS = 4;
+
+size_t plan_area_bytes(int ncls) { return up256(2 * sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4); }
+
 size_t group_fixed_bytes(int ncls, int K)
 {
-    return up256((size_t)ncls * sizeof(RcdClass)) + up256(2 * sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4) +
+    return up256((size_t)ncls * sizeof(RcdClass)) + RCD_MAX_LANES * plan_area_bytes(ncls) +
            up256((size_t)ncls * K * sizeof(double));
 }
 
 struct Group {
     RcdClass *classes_dev = nullptr;
-    RcdPlan *plan_dev = nullptr;
+    RcdPlan *plan_dev = nullptr;                 // = plan_area[0]
+    RcdPlan *plan_area[RCD_MAX_LANES] = {};      // one plan record per lane (only the owner of the workspace slice has them all)
     double *obj_dev = nullptr;
     std::vector<RcdClass> host;   // kept alive until the stream has consumed it
     int K = 0;
@@ -148,90 +158,52 @@ int ensure_pinned()
 {
     if (!g_pinned) {
         void *p = nullptr;
-        HIP_TRY(hipHostMalloc(&p, 4 * sizeof(RcdPlan), hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc(&p, RCD_MAX_LANES * RCD_SLOTS * 2 * sizeof(RcdPlan), hipHostMallocDefault));
         g_pinned = (RcdPlan *)p;
     }
     return RCD_OK;
 }
 
-// Upload the descriptors, reset the state and run rounds until every class of
-// the group is finished.  Fills g.obj_dev.  Accumulates g_stats.
-int run_group(Group &g, hipStream_t stream)
+// Streams of the library's own, for groups of classes that advance side by side.
+int ensure_side_streams(int count)
 {
-    const int ncls = (int)g.host.size();
-    RCD_TRY(ensure_pinned());
-    const int target_total = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
-    const int per_class = std::max(1, target_total / ncls);
-    int items_ub = 0;
-    for (RcdClass &c : g.host) {
-        c.target_items = per_class;
-        items_ub += sweep_items_bound(c);
-    }
-    RcdPlan plan0;
-    memset(&plan0, 0, sizeof plan0);
-    plan0.ncls = ncls;
-    // the validation kernels may already have raised plans[0].bad: keep it
-    HIP_TRY(hipMemcpyAsync(&g.plan_dev[0].ncls, &plan0.ncls, sizeof(int32_t) * 5, hipMemcpyHostToDevice, stream));
-    HIP_TRY(hipMemcpyAsync(&g.plan_dev[1], &plan0, sizeof plan0, hipMemcpyHostToDevice, stream));
-    HIP_TRY(hipMemcpyAsync(g.classes_dev, g.host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
-    hipLaunchKernelGGL(rcd_k_init, dim3(64, ncls), dim3(256), 0, stream, g.classes_dev);
-    int max_n = 0;
-    for (const RcdClass &c : g.host) max_n = std::max(max_n, c.n);
-    const dim3 apply_grid((unsigned)((max_n + 255) / 256), (unsigned)ncls);
-    // step loop number 1 (the bootstrap) and its apply; step loop r+2 runs inside round r
-    hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev, g.plan_dev);
+    for (int i = 0; i < count && i < RCD_MAX_LANES; ++i)
+        if (!g_side[i]) HIP_TRY(hipStreamCreateWithFlags(&g_side[i], hipStreamNonBlocking));
+    return RCD_OK;
+}
 
-    hipEvent_t ev[2];
-    HIP_TRY(hipEventCreateWithFlags(&ev[0], hipEventDisableTiming));
-    HIP_TRY(hipEventCreateWithFlags(&ev[1], hipEventDisableTiming));
-    const int rounds = env_int("RCD_ROUNDS_PER_BATCH", 16, 1, 1024);
-    // a group is homogeneous: all stored, or all recomputed from the same X
-    const RcdClass &first = g.host[0];
-    const bool recompute = first.mode == RCD_MODE_RECOMPUTE;
-    const int esz = first.dt == RCD_F32 ? 4 : 2;
-    const bool fast = recompute && (reinterpret_cast<uintptr_t>(first.X) & 15) == 0 &&
-                      ((first.ldx64 * esz) % 16) == 0 && ((int64_t)first.d * esz) % sim::ROWB == 0;
-    // One launch per round (sweep + step loops fused) pays off when few classes are in
-    // flight; with many, the sweep is bandwidth-bound and the step loops get their own launch.
-    const bool fused = env_int("RCD_FUSED", ncls <= 2 ? 1 : 0, 0, 1) != 0;
+// One group of classes on one stream.  The host keeps a few batches of rounds
+// queued ahead of the device: start(), then enqueue_batch() while fewer than
+// `depth` batches are unread and poll() to read the oldest one's progress record,
+// until finished; then finish().  Several lanes can be driven in an interleaved
+// way; each keeps to its own stream, descriptors, plans and progress slots.
+struct Lane {
+    Group *g = nullptr;
+    hipStream_t stream = nullptr;
+    int slot = 0;            // which pinned progress slots are this lane's
+    int ncls = 0, rounds = 16, items_ub = 0, round_no = 0;
+    bool recompute = false, fused = false, prof = false, finished = false;
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
     void (*apply_rc)(RcdClass *, int) = nullptr;
-    if (recompute) {
-        if (first.dt == RCD_F32) {
-            round_rc = fused ? (fast ? rcd_k_round_rc<float, true, true> : rcd_k_round_rc<float, false, true>)
-                             : (fast ? rcd_k_round_rc<float, true, false> : rcd_k_round_rc<float, false, false>);
-            apply_rc = rcd_k_apply_rc<float>;
-        } else {
-            round_rc = fused ? (fast ? rcd_k_round_rc<__bf16, true, true> : rcd_k_round_rc<__bf16, false, true>)
-                             : (fast ? rcd_k_round_rc<__bf16, true, false> : rcd_k_round_rc<__bf16, false, false>);
-            apply_rc = rcd_k_apply_rc<__bf16>;
-        }
+    void (*round_st)(RcdClass *, RcdPlan *, int) = nullptr;
+    dim3 apply_grid, apply_rc_grid;
+    hipEvent_t ev[RCD_SLOTS] = {};
+    int64_t launches = 0, max_batches = 0;
+    int64_t batch = 0;       // batches enqueued
+    int64_t polled = 0;      // batches whose progress record has been read
+    int64_t prof_done = 0;   // batches whose timing events have been read
+
+    RcdPlan *pinned(int64_t b) const { return g_pinned + 2 * (RCD_SLOTS * slot + (int)(b % RCD_SLOTS)); }
+
+    void launch_apply(int rn)
+    {
+        if (recompute) hipLaunchKernelGGL(apply_rc, apply_rc_grid, dim3(256), 0, stream, g->classes_dev, rn);
+        else hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g->classes_dev, rn);
     }
-    void (*round_st)(RcdClass *, RcdPlan *, int) =
-        fused ? (g.K <= 4 ? rcd_k_round<4, true> : (g.K <= 8 ? rcd_k_round<8, true> : rcd_k_round<16, true>))
-              : (g.K <= 4 ? rcd_k_round<4, false> : (g.K <= 8 ? rcd_k_round<8, false> : rcd_k_round<16, false>));
-    const dim3 apply_rc_grid((unsigned)((max_n + 3) / 4), (unsigned)ncls);
-    auto launch_apply = [&](int rn) {
-        if (recompute) hipLaunchKernelGGL(apply_rc, apply_rc_grid, dim3(256), 0, stream, g.classes_dev, rn);
-        else hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g.classes_dev, rn);
-    };
-    int64_t launches = 3;
-    int round_no = 0;
-    launch_apply(1);
-    int rc = RCD_OK;
-    const bool prof = g_profile_on != 0;
-    if (prof) {
-        for (int s = 0; s < 2; ++s)
-            while ((int)g_prof_ev[s].size() < 3 * rounds + 1) {
-                hipEvent_t e;
-                HIP_TRY(hipEventCreate(&e));
-                g_prof_ev[s].push_back(e);
-            }
-    }
-    int64_t prof_done = 0;   // batches whose events have been read
-    int64_t last_batch = -1; // last batch that was enqueued in full
-    auto read_events = [&](int64_t batch) {
-        std::vector<hipEvent_t> &e = g_prof_ev[batch & 1];
+
+    void read_events(int64_t b)
+    {
+        std::vector<hipEvent_t> &e = g_prof_ev[b % RCD_SLOTS];
         for (int r = 0; r < rounds; ++r) {
             float ms = 0.f;
             if (hipEventElapsedTime(&ms, e[3 * r], e[3 * r + 1]) == hipSuccess) g_prof[1] += ms;
@@ -239,32 +211,108 @@ int run_group(Group &g, hipStream_t stream)
             if (hipEventElapsedTime(&ms, e[3 * r + 2], e[3 * r + 3]) == hipSuccess) g_prof[2] += ms;
         }
         g_prof[3] += rounds;
-    };
-    // every round takes at least one step in every unfinished class, so this
-    // many batches always suffice; running past it means a defect, not work
-    int64_t max_total = 0;
-    for (const RcdClass &c : g.host) max_total = std::max<int64_t>(max_total, c.total);
-    const int64_t max_batches = (max_total + 2) / rounds + 3;
-    for (int64_t b = 0;; ++b) {
+    }
+
+    // Upload the descriptors, reset the state, run the first step loop.
+    // target_total: sweep workgroups per round this lane aims at.
+    int start(Group &group, hipStream_t s, int slot_, int target_total, bool profile)
+    {
+        g = &group;
+        stream = s;
+        slot = slot_;
+        prof = profile;
+        ncls = (int)g->host.size();
+        const int per_class = std::max(1, target_total / ncls);
+        items_ub = 0;
+        int max_n = 0;
+        int64_t max_total = 0;
+        for (RcdClass &c : g->host) {
+            c.target_items = per_class;
+            items_ub += sweep_items_bound(c);
+            max_n = std::max(max_n, c.n);
+            max_total = std::max<int64_t>(max_total, c.total);
+        }
+        rounds = env_int("RCD_ROUNDS_PER_BATCH", 16, 1, 1024);
+        // every round takes at least one step in every unfinished class, so this
+        // many batches (plus those queued ahead) always suffice; running past it means a defect, not work
+        max_batches = (max_total + 2) / rounds + 3 + RCD_SLOTS;
+        RcdPlan plan0;
+        memset(&plan0, 0, sizeof plan0);
+        plan0.ncls = ncls;
+        // the validation kernels may already have raised plans[0].bad: keep it
+        HIP_TRY(hipMemcpyAsync(&g->plan_dev[0].ncls, &plan0.ncls, sizeof(int32_t) * 5, hipMemcpyHostToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(&g->plan_dev[1], &plan0, sizeof plan0, hipMemcpyHostToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(g->classes_dev, g->host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
+        hipLaunchKernelGGL(rcd_k_init, dim3(64, ncls), dim3(256), 0, stream, g->classes_dev);
+        apply_grid = dim3((unsigned)((max_n + 255) / 256), (unsigned)ncls);
+        apply_rc_grid = dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls);
+        // step loop number 1 (the bootstrap) and its apply; step loop r+2 runs inside round r
+        hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev);
+
+        for (int i = 0; i < RCD_SLOTS; ++i) HIP_TRY(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
+        // a group is homogeneous: all stored, or all recomputed from the same X
+        const RcdClass &first = g->host[0];
+        recompute = first.mode == RCD_MODE_RECOMPUTE;
+        const int esz = first.dt == RCD_F32 ? 4 : 2;
+        const bool fast = recompute && (reinterpret_cast<uintptr_t>(first.X) & 15) == 0 &&
+                          ((first.ldx64 * esz) % 16) == 0 && ((int64_t)first.d * esz) % sim::ROWB == 0;
+        // One launch per round (sweep + step loops fused) pays off when few classes are in
+        // flight; with many, the sweep is bandwidth-bound and the step loops get their own launch.
+        fused = env_int("RCD_FUSED", ncls <= 2 ? 1 : 0, 0, 1) != 0;
+        if (recompute) {
+            if (first.dt == RCD_F32) {
+                round_rc = fused ? (fast ? rcd_k_round_rc<float, true, true> : rcd_k_round_rc<float, false, true>)
+                                 : (fast ? rcd_k_round_rc<float, true, false> : rcd_k_round_rc<float, false, false>);
+                apply_rc = rcd_k_apply_rc<float>;
+            } else {
+                round_rc = fused ? (fast ? rcd_k_round_rc<__bf16, true, true> : rcd_k_round_rc<__bf16, false, true>)
+                                 : (fast ? rcd_k_round_rc<__bf16, true, false> : rcd_k_round_rc<__bf16, false, false>);
+                apply_rc = rcd_k_apply_rc<__bf16>;
+            }
+        }
+        const int K = g->K;
+        round_st = fused ? (K <= 4 ? rcd_k_round<4, true> : (K <= 8 ? rcd_k_round<8, true> : rcd_k_round<16, true>))
+                         : (K <= 4 ? rcd_k_round<4, false> : (K <= 8 ? rcd_k_round<8, false> : rcd_k_round<16, false>));
+        launches = 3;
+        round_no = 0;
+        launch_apply(1);
+        if (prof) {
+            for (int i = 0; i < RCD_SLOTS; ++i)
+                while ((int)g_prof_ev[i].size() < 3 * rounds + 1) {
+                    hipEvent_t e;
+                    HIP_TRY(hipEventCreate(&e));
+                    g_prof_ev[i].push_back(e);
+                }
+        }
+        batch = 0;
+        polled = 0;
+        prof_done = 0;
+        finished = false;
+        return RCD_OK;
+    }
+
+    // One batch of rounds, then a copy of the progress record for the host.
+    int enqueue_batch()
+    {
+        const int64_t b = batch;
         if (b > max_batches) {
             snprintf(g_hip_err, sizeof g_hip_err, "greedy made no progress within %lld batches", (long long)max_batches);
-            rc = RCD_ERR_HIP;
-            break;
+            return RCD_ERR_HIP;
         }
-        std::vector<hipEvent_t> *pe = prof ? &g_prof_ev[b & 1] : nullptr;
+        std::vector<hipEvent_t> *pe = prof ? &g_prof_ev[b % RCD_SLOTS] : nullptr;
         if (pe) (void)hipEventRecord((*pe)[0], stream);
         for (int r = 0; r < rounds; ++r) {
             const int buf = fused ? (round_no & 1) : 0;
             if (recompute)
-                hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), 0, stream, g.classes_dev, g.plan_dev, buf);
+                hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), 0, stream, g->classes_dev, g->plan_dev, buf);
             else
-                hipLaunchKernelGGL(round_st, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
-                                   g.plan_dev, buf);
+                hipLaunchKernelGGL(round_st, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g->classes_dev,
+                                   g->plan_dev, buf);
             ++round_no;
             if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
             if (!fused)
-                hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g.classes_dev,
-                                   g.plan_dev);
+                hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                                   g->plan_dev);
             if (pe) (void)hipEventRecord((*pe)[3 * r + 2], stream);
             launch_apply(round_no + 1);
             if (pe) (void)hipEventRecord((*pe)[3 * r + 3], stream);
@@ -273,60 +321,154 @@ int run_group(Group &g, hipStream_t stream)
         hipError_t le = hipGetLastError();
         if (le != hipSuccess) {
             snprintf(g_hip_err, sizeof g_hip_err, "kernel launch -> %s", hipGetErrorString(le));
-            rc = RCD_ERR_HIP;
-            break;
+            return RCD_ERR_HIP;
         }
-        hipError_t e1 = hipMemcpyAsync(&g_pinned[2 * (b & 1)], g.plan_dev, 2 * sizeof(RcdPlan), hipMemcpyDeviceToHost, stream);
-        hipError_t e2 = hipEventRecord(ev[b & 1], stream);
+        hipError_t e1 = hipMemcpyAsync(pinned(b), g->plan_dev, 2 * sizeof(RcdPlan), hipMemcpyDeviceToHost, stream);
+        hipError_t e2 = hipEventRecord(ev[b % RCD_SLOTS], stream);
         if (e1 != hipSuccess || e2 != hipSuccess) {
             snprintf(g_hip_err, sizeof g_hip_err, "progress readback -> %s",
                      hipGetErrorString(e1 != hipSuccess ? e1 : e2));
-            rc = RCD_ERR_HIP;
-            break;
+            return RCD_ERR_HIP;
         }
-        if (b >= 1) {
-            hipError_t e3 = hipEventSynchronize(ev[(b - 1) & 1]);
-            if (e3 != hipSuccess) {
-                snprintf(g_hip_err, sizeof g_hip_err, "hipEventSynchronize -> %s", hipGetErrorString(e3));
-                rc = RCD_ERR_HIP;
-                break;
+        batch = b + 1;
+        return RCD_OK;
+    }
+
+    // Read the progress record of the oldest unread batch: waiting for it (block), or only
+    // if it has already arrived.  *got says whether a record was read.
+    int poll(bool block, bool *got)
+    {
+        *got = false;
+        if (polled >= batch) return RCD_OK;
+        hipEvent_t e = ev[polled % RCD_SLOTS];
+        hipError_t q = block ? hipEventSynchronize(e) : hipEventQuery(e);
+        if (q == hipErrorNotReady) return RCD_OK;
+        if (q != hipSuccess) {
+            snprintf(g_hip_err, sizeof g_hip_err, "waiting for a batch of rounds -> %s", hipGetErrorString(q));
+            return RCD_ERR_HIP;
+        }
+        *got = true;
+        if (prof) { read_events(polled); prof_done = polled + 1; }
+        const RcdPlan *seen = pinned(polled);
+        ++polled;
+        if (seen[0].bad) { finished = true; return RCD_ERR_BAD_SIMILARITY; }
+        if (std::max(seen[0].ndone, seen[1].ndone) >= ncls) finished = true;
+        return RCD_OK;
+    }
+
+    // Drain the stream; on success compute the objectives and collect the counters.
+    int finish(int rc)
+    {
+        hipError_t es = hipStreamSynchronize(stream);
+        if (prof && es == hipSuccess && rc == RCD_OK)
+            for (int64_t b = prof_done; b < batch; ++b) read_events(b);
+        for (int i = 0; i < RCD_SLOTS; ++i) {
+            if (ev[i]) (void)hipEventDestroy(ev[i]);
+            ev[i] = nullptr;
+        }
+        if (rc != RCD_OK) return rc;
+        if (es != hipSuccess) {
+            snprintf(g_hip_err, sizeof g_hip_err, "hipStreamSynchronize -> %s", hipGetErrorString(es));
+            return RCD_ERR_HIP;
+        }
+        hipLaunchKernelGGL(rcd_k_objective, dim3(g->K, ncls), dim3(256), 0, stream, (const RcdClass *)g->classes_dev,
+                           g->obj_dev, g->K);
+        HIP_TRY(hipMemcpyAsync(g->host.data(), g->classes_dev, sizeof(RcdClass) * ncls, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        for (const RcdClass &c : g->host) {
+            g_stats[0] += c.stat_steps;
+            g_stats[1] += c.stat_sweeps;
+            g_stats[2] += c.stat_entries;
+            g_stats[3] += c.stat_useful;
+            g_stats[5] += c.stat_computed;
+            g_stats[6] += c.stat_ticks;
+        }
+        g_stats[4] += launches + 1;
+        return RCD_OK;
+    }
+};
+
+// Run every group to completion.  One group: on the caller's stream.  Several:
+// each on a stream of the library's own, ordered after what the caller's stream
+// holds so far; the host feeds them in turn, so that one group's step loops and
+// coverage updates (latency-bound, a few workgroups) overlap the other groups'
+// sweeps (bandwidth-bound, the whole chip).  Returns after all of them finished:
+// work the caller enqueues afterwards is ordered behind them.  Fills each
+// group's obj_dev and accumulates g_stats.
+int run_groups(std::vector<Group> &groups, hipStream_t stream)
+{
+    const int nl = (int)groups.size();
+    if (nl < 1) return RCD_OK;
+    if (nl > RCD_MAX_LANES) return RCD_ERR_INVALID_ARG;
+    RCD_TRY(ensure_pinned());
+    const int target_total = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
+    std::vector<Lane> lanes(nl);
+    int rc = RCD_OK;
+    int started = 0;
+    if (nl == 1) {
+        rc = lanes[0].start(groups[0], stream, 0, target_total, g_profile_on != 0);
+        started = 1;
+    } else {
+        RCD_TRY(ensure_side_streams(nl));
+        hipEvent_t ready;
+        HIP_TRY(hipEventCreateWithFlags(&ready, hipEventDisableTiming));
+        hipError_t e = hipEventRecord(ready, stream);
+        for (int i = 0; i < nl && e == hipSuccess; ++i) e = hipStreamWaitEvent(g_side[i], ready, 0);
+        (void)hipEventDestroy(ready);
+        if (e != hipSuccess) {
+            snprintf(g_hip_err, sizeof g_hip_err, "stream fork -> %s", hipGetErrorString(e));
+            return RCD_ERR_HIP;
+        }
+        const int per_lane = std::max(256, target_total * 2 / (nl + 1));
+        for (int i = 0; i < nl && rc == RCD_OK; ++i) {
+            rc = lanes[i].start(groups[i], g_side[i], i, per_lane, false);
+            ++started;
+        }
+    }
+    // One lane: one batch ahead, blocking waits.  Several: up to three batches queued per
+    // lane, so that no lane runs dry while the host looks after another one; records are
+    // read as they arrive.
+    const int depth = nl == 1 ? 2 : RCD_SLOTS - 1;
+    while (rc == RCD_OK) {
+        bool any = false, progressed = false;
+        for (int i = 0; i < nl && rc == RCD_OK; ++i) {
+            Lane &ln = lanes[i];
+            if (ln.finished) continue;
+            any = true;
+            while (rc == RCD_OK && ln.batch - ln.polled < depth) {
+                rc = ln.enqueue_batch();
+                progressed = true;
             }
-            if (prof) { read_events(b - 1); prof_done = b; }
-            const RcdPlan *seen = &g_pinned[2 * ((b - 1) & 1)];
-            if (seen[0].bad) { rc = RCD_ERR_BAD_SIMILARITY; last_batch = b; break; }
-            if (std::max(seen[0].ndone, seen[1].ndone) >= ncls) { last_batch = b; break; }
+            bool got = false;
+            if (rc == RCD_OK) rc = ln.poll(nl == 1, &got);
+            progressed |= got;
         }
+        if (!any) break;
+        if (!progressed) std::this_thread::yield();
     }
-    hipError_t es = hipStreamSynchronize(stream);
-    if (prof && es == hipSuccess && rc == RCD_OK)
-        for (int64_t b = prof_done; b <= last_batch; ++b) read_events(b);
-    hipEventDestroy(ev[0]);
-    hipEventDestroy(ev[1]);
-    if (rc != RCD_OK) return rc;
-    if (es != hipSuccess) {
-        snprintf(g_hip_err, sizeof g_hip_err, "hipStreamSynchronize -> %s", hipGetErrorString(es));
-        return RCD_ERR_HIP;
+    // every started lane is drained, whatever happened, before the workspace is let go
+    for (int i = 0; i < started; ++i) {
+        const int r = lanes[i].finish(rc);
+        if (rc == RCD_OK) rc = r;
     }
-    hipLaunchKernelGGL(rcd_k_objective, dim3(g.K, ncls), dim3(256), 0, stream, (const RcdClass *)g.classes_dev,
-                       g.obj_dev, g.K);
-    HIP_TRY(hipMemcpyAsync(g.host.data(), g.classes_dev, sizeof(RcdClass) * ncls, hipMemcpyDeviceToHost, stream));
-    HIP_TRY(hipStreamSynchronize(stream));
-    for (const RcdClass &c : g.host) {
-        g_stats[0] += c.stat_steps;
-        g_stats[1] += c.stat_sweeps;
-        g_stats[2] += c.stat_entries;
-        g_stats[3] += c.stat_useful;
-        g_stats[5] += c.stat_computed;
-        g_stats[6] += c.stat_ticks;
-    }
-    g_stats[4] += launches + 1;
-    return RCD_OK;
+    return rc;
+}
+
+int run_group(Group &g, hipStream_t stream)
+{
+    std::vector<Group> one(1);
+    one[0] = std::move(g);
+    const int rc = run_groups(one, stream);
+    g = std::move(one[0]);
+    return rc;
 }
 
 bool carve_group_fixed(Carver &cv, Group &g, int ncls, int K)
 {
     g.classes_dev = cv.take<RcdClass>((size_t)ncls);
-    g.plan_dev = reinterpret_cast<RcdPlan *>(cv.take<char>(2 * sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4));
+    for (int i = 0; i < RCD_MAX_LANES; ++i)
+        g.plan_area[i] = reinterpret_cast<RcdPlan *>(cv.take<char>(plan_area_bytes(ncls)));
+    g.plan_dev = g.plan_area[0];
     g.obj_dev = cv.take<double>((size_t)ncls * K);
     g.K = K;
     return !cv.fail;
@@ -697,7 +839,8 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
             g.host.resize(live);
             std::vector<int> cls_of(live);
             int gi = 0;
-            HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
+            for (int i = 0; i < RCD_MAX_LANES; ++i)
+                HIP_TRY(hipMemsetAsync(g.plan_area[i], 0, 2 * sizeof(RcdPlan), stream));
             hipEvent_t sim_ev[2] = {nullptr, nullptr};
             if (g_profile_on) {
                 HIP_TRY(hipEventCreate(&sim_ev[0]));
@@ -723,7 +866,33 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
                 cls_of[gi++] = l;
             }
             if (g_profile_on) HIP_TRY(hipEventRecord(sim_ev[1], stream));
-            RCD_TRY(run_group(g, stream));
+            // Stored mode: deal the classes to a few lanes of about equal work (cost ~ n^3),
+            // contiguous in the descriptor array.  A recomputed sweep keeps the matrix cores
+            // busy for milliseconds per round, so there is nothing for a second lane to hide.
+            int nl = 1;
+            if (stored && !g_profile_on) nl = std::min(live, env_int("RCD_LANES", 3, 1, RCD_MAX_LANES));
+            std::vector<Group> lanes(nl);
+            {
+                std::vector<double> cum(live + 1, 0.0);
+                for (int i = 0; i < live; ++i) {
+                    const double n = (double)g.host[i].n;
+                    cum[i + 1] = cum[i] + n * n * n + 1.0;
+                }
+                int a = 0;
+                for (int i = 0; i < nl; ++i) {
+                    int b = a + 1;   // at least one class per lane, and leave one for each lane after this
+                    while (b < live - (nl - 1 - i) && cum[b] < cum[live] * (i + 1) / nl) ++b;
+                    if (i == nl - 1) b = live;
+                    Group &sub = lanes[i];
+                    sub.classes_dev = g.classes_dev + a;
+                    sub.plan_dev = sub.plan_area[0] = g.plan_area[i];
+                    sub.obj_dev = g.obj_dev + (size_t)a * K;
+                    sub.K = K;
+                    sub.host.assign(g.host.begin() + a, g.host.begin() + b);
+                    a = b;
+                }
+            }
+            RCD_TRY(run_groups(lanes, stream));
             if (g_profile_on) {
                 float ms = 0.f;
                 if (hipEventElapsedTime(&ms, sim_ev[0], sim_ev[1]) == hipSuccess) g_prof[4] += ms;
