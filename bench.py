@@ -199,7 +199,7 @@ def main():
     sweep_bytes = 4.0 * pstats["entries_streamed"]
     achieved = sweep_bytes / (prof["sweep_ms"] * 1e-3) / 1e9 if prof["sweep_ms"] > 0 else 0.0
     roofline = {
-        "kernel": "rcd_k_round (gain sweep of all stale blocks + chunk finalisation)",
+        "kernel": "rcd_k_sweep_rows (gain sweep of all stale blocks, stored similarity)",
         "bound": "hbm",
         "achieved": achieved,
         "peak": HBM_PEAK_GBS,

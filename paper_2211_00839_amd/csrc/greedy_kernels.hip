@@ -1,15 +1,15 @@
 // Kernels of the class greedy (Algorithm 1 of arXiv 2211.00839, inner while loop,
 // with the facility-location function of Section 4) for gfx950.
 //
-// Data layout.  M is the class's similarity matrix, row j = covered sample j in
-// the class's original order, column p = candidate perm[p].  Only the first nR
-// columns are live: when a candidate is taken its column is overwritten by the
-// last live column, so a sweep reads exactly n x nR entries.  Because S is
-// symmetric, "row j, 256 consecutive candidates" is a contiguous 1 KB read and
-// each lane owns its candidates' sums outright: cur_k(j) is wave-uniform and
-// comes through scalar loads, and no cross-lane reduction exists anywhere in
-// the sweep.
+// Data layout, stored similarity.  M[v][j] = S(j, v): row v holds candidate v's
+// similarity to every sample j of the class, contiguous (for the symmetric matrix
+// the similarity builder writes, M is simply S).  M is never written.  The
+// unassigned candidates are the list perm[0 .. nR): a sweep streams exactly those
+// nR rows, and taking a candidate moves the last list entry into its place.
+// The recomputed mode (other file) shares the step loop and the arrival helpers.
 #include <hip/hip_runtime.h>
+#include <cstddef>
+#include <type_traits>
 #include "rcd_state.h"
 
 namespace {
@@ -106,94 +106,130 @@ __device__ __forceinline__ int find_class(const int32_t *prefix, int ncls, int i
 }
 
 // ---------------------------------------------------------------------------
-// Gain sweep (GreedyStep's objective for every candidate and every stale block):
-//   part[chunk][k][p] = sum_{j in chunk} max(0, M[j][p] - cur_k(j))
-// One workgroup = 8 waves on one 256-column tile; wave w takes the w-th eighth
-// of the chunk's rows.  KS = number of blocks evaluated (compile-time so the
-// accumulators stay in registers).
+// Gain sweep, stored similarity (GreedyStep's objective for every candidate and
+// every stale block):
+//   part[c][k][p] = sum_{j in chunk c} max(0, M[perm[p]][j] - cur_k(j))
+// One wave streams one candidate's row (contiguous) at a time; the workgroup's
+// 16 waves share the coverage vectors of the evaluated blocks, staged in LDS for
+// the chunk of j the pass covers.  A lane keeps one running sum per block, the
+// wave adds its 64 lanes in a fixed order at the end of the row, and lane 0
+// writes the result: no partial sums between workgroups, nothing to finalise.
+// KS = number of blocks evaluated (compile-time so the sums stay in registers).
+// The workgroup is the w-th of W that serve this class.
 // ---------------------------------------------------------------------------
-template <int KS>
-__device__ __forceinline__ void sweep_body(const RcdClass &st, int tile, int chunk, float4 *lds)
-{
-    const int lane = threadIdx.x & 63;
-    // the wave index is the same in all 64 lanes: tell the compiler, so that row
-    // counters and coverage addresses live in scalar registers
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int ld = st.ld;
-    const int rpw = st.rpc / RCD_SWEEP_WAVES;
-    const int row0 = chunk * st.rpc + wave * rpw;
-    const int row1 = min(st.n, row0 + rpw);
-    const int nneed = st.nneed;
+typedef const int32_t __attribute__((address_space(4))) *cci32;
+typedef float __attribute__((address_space(3))) *lf32;
+typedef const f32x4 __attribute__((address_space(3))) *lcf32x4;
 
-    // lanes whose four columns are all dead (past the last live candidate) re-read column 0
-    // instead: one shared line per row rather than a wasted fetch of their own
-    const int col0 = tile * RCD_TILE + lane * 4;
-    const gcf32 Mp = (gcf32)st.M + (col0 < st.nR ? col0 : 0);
-    ccf32 cp[KS];
+// Sum over the 64 lanes, same value in every lane, fixed order:
+// pairs, quads, halves of a 16-lane row, the row, then the four rows.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    int x;
+    x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true);    // quad_perm 1,0,3,2
+    v += __int_as_float(x);
+    x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true);    // quad_perm 2,3,0,1
+    v += __int_as_float(x);
+    x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true);   // row_half_mirror
+    v += __int_as_float(x);
+    x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true);   // row_mirror
+    v += __int_as_float(x);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+template <int KS>
+__device__ __forceinline__ void sweep_rows(const RcdClass &st, int w, int W, float *lds)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    // the wave index is the same in all 64 lanes: tell the compiler, so that row
+    // counters and row addresses live in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the descriptor is the same for the whole workgroup: keep its fields in scalar registers
+    const int ld = __builtin_amdgcn_readfirstlane(st.ld), nR = __builtin_amdgcn_readfirstlane(st.nR);
+    const int K = __builtin_amdgcn_readfirstlane(st.K), nneed = __builtin_amdgcn_readfirstlane(st.nneed);
+    const int JC = __builtin_amdgcn_readfirstlane(st.rpc), C = __builtin_amdgcn_readfirstlane(st.C);
     int kb[KS];
 #pragma unroll
-    for (int i = 0; i < KS; ++i) {
-        kb[i] = st.need[i < nneed ? i : nneed - 1];
-        cp[i] = (ccf32)st.cur + (size_t)kb[i] * ld;
-    }
-    float4 acc[KS];
-#pragma unroll
-    for (int i = 0; i < KS; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < KS; ++i) kb[i] = __builtin_amdgcn_readfirstlane(st.need[i < nneed ? i : nneed - 1]);
+    const gcf32 M = (gcf32)st.M;
+    const gcf32 cur = (gcf32)st.cur;
+    const cci32 perm = (cci32)st.perm;
+    const gf32 part = (gf32)st.part;
+    const int stride = W * RCD_SWEEP_WAVES;
+    const lf32 lcur = (lf32)lds;
 
-    int j = row0;
-    for (; j + 4 <= row1; j += 4) {
-        const f32x4 s0 = *(gcf32x4)(Mp + (size_t)(j + 0) * ld);
-        const f32x4 s1 = *(gcf32x4)(Mp + (size_t)(j + 1) * ld);
-        const f32x4 s2 = *(gcf32x4)(Mp + (size_t)(j + 2) * ld);
-        const f32x4 s3 = *(gcf32x4)(Mp + (size_t)(j + 3) * ld);
+    for (int c = 0; c < C; ++c) {
+        const int j0 = c * JC;
+        const int len = min(JC, ld - j0);   // a multiple of 256
+        if (c > 0) __syncthreads();
 #pragma unroll
         for (int i = 0; i < KS; ++i) {
-            const float c0 = cp[i][j], c1 = cp[i][j + 1], c2 = cp[i][j + 2], c3 = cp[i][j + 3];
-            acc[i].x += clamp01(s0.x - c0); acc[i].y += clamp01(s0.y - c0);
-            acc[i].z += clamp01(s0.z - c0); acc[i].w += clamp01(s0.w - c0);
-            acc[i].x += clamp01(s1.x - c1); acc[i].y += clamp01(s1.y - c1);
-            acc[i].z += clamp01(s1.z - c1); acc[i].w += clamp01(s1.w - c1);
-            acc[i].x += clamp01(s2.x - c2); acc[i].y += clamp01(s2.y - c2);
-            acc[i].z += clamp01(s2.z - c2); acc[i].w += clamp01(s2.w - c2);
-            acc[i].x += clamp01(s3.x - c3); acc[i].y += clamp01(s3.y - c3);
-            acc[i].z += clamp01(s3.z - c3); acc[i].w += clamp01(s3.w - c3);
+            const gcf32 src = cur + (size_t)kb[i] * ld + j0;
+            for (int e = tid * 4; e < len; e += RCD_SWEEP_THREADS * 4)
+                *(f32x4 __attribute__((address_space(3))) *)(lcur + i * JC + e) = *(gcf32x4)(src + e);
         }
-    }
-    for (; j < row1; ++j) {
-        const f32x4 s0 = *(gcf32x4)(Mp + (size_t)j * ld);
-#pragma unroll
-        for (int i = 0; i < KS; ++i) {
-            const float c0 = cp[i][j];
-            acc[i].x += clamp01(s0.x - c0); acc[i].y += clamp01(s0.y - c0);
-            acc[i].z += clamp01(s0.z - c0); acc[i].w += clamp01(s0.w - c0);
-        }
-    }
-
-    // Add the waves' sums in wave order, four blocks at a time.
-    // lds is [wave][block-in-group 4][lane 64] float4.
-    const gf32 part = (gf32)st.part + (size_t)chunk * st.K * ld + (size_t)tile * RCD_TILE + lane * 4;
-#pragma unroll
-    for (int g0 = 0; g0 < KS; g0 += 4) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (g0 + i < KS) lds[(wave * 4 + i) * 64 + lane] = acc[g0 + i];
         __syncthreads();
-        const int mine = g0 + wave;
-        if (wave < 4 && mine < KS && mine < nneed) {
-            float4 a = lds[(0 * 4 + wave) * 64 + lane];
+
+        int p = w * RCD_SWEEP_WAVES + wave;
+        int v = p < nR ? perm[p] : 0;
+        while (p < nR) {
+            const int pn = p + stride;
+            const int vn = pn < nR ? perm[pn] : 0;   // next row's sample, fetched under this row's stream
+            const gcf32 row = M + (size_t)v * ld + j0 + lane * 4;
+            f32x4 acc[KS];
 #pragma unroll
-            for (int w = 1; w < RCD_SWEEP_WAVES; ++w) {
-                const float4 b = lds[(w * 4 + wave) * 64 + lane];
-                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            for (int i = 0; i < KS; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            int s = 0;
+            // U row pieces of 1 KB in flight per wave (fewer when many blocks' sums fill the registers)
+            constexpr int U = KS <= 8 ? 4 : 2;
+            for (; s + 256 * U <= len; s += 256 * U) {
+                f32x4 m[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) m[u] = *(gcf32x4)(row + s + 256 * u);
+#pragma unroll
+                for (int i = 0; i < KS; ++i) {
+                    const lcf32x4 cp = (lcf32x4)(lcur + i * JC + s + lane * 4);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const f32x4 cc = cp[64 * u];
+                        if constexpr (KS > 8) {
+                            // one running sum per block, or sixteen blocks would not fit the registers
+                            acc[i].x += (clamp01(m[u].x - cc.x) + clamp01(m[u].y - cc.y)) +
+                                        (clamp01(m[u].z - cc.z) + clamp01(m[u].w - cc.w));
+                        } else {
+                            acc[i].x += clamp01(m[u].x - cc.x); acc[i].y += clamp01(m[u].y - cc.y);
+                            acc[i].z += clamp01(m[u].z - cc.z); acc[i].w += clamp01(m[u].w - cc.w);
+                        }
+                    }
+                }
             }
-            int kmine = kb[0];
+            for (; s < len; s += 256) {
+                const f32x4 m0 = *(gcf32x4)(row + s);
 #pragma unroll
-            for (int i = 0; i < KS; ++i)
-                if (i == mine) kmine = kb[i];
-            const gf32 dst = part + (size_t)kmine * ld;
-            dev_store4(dst, a.x, a.y, a.z, a.w);
+                for (int i = 0; i < KS; ++i) {
+                    const f32x4 c0 = *(lcf32x4)(lcur + i * JC + s + lane * 4);
+                    if constexpr (KS > 8) {
+                        acc[i].x += (clamp01(m0.x - c0.x) + clamp01(m0.y - c0.y)) +
+                                    (clamp01(m0.z - c0.z) + clamp01(m0.w - c0.w));
+                    } else {
+                        acc[i].x += clamp01(m0.x - c0.x); acc[i].y += clamp01(m0.y - c0.y);
+                        acc[i].z += clamp01(m0.z - c0.z); acc[i].w += clamp01(m0.w - c0.w);
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < KS; ++i) {
+                const float t = wave_sum((acc[i].x + acc[i].y) + (acc[i].z + acc[i].w));
+                if (lane == 0 && i < nneed) part[((size_t)c * K + kb[i]) * ld + p] = t;
+            }
+            p = pn;
+            v = vn;
         }
-        __syncthreads();
     }
 }
 
@@ -529,102 +565,419 @@ rcd_k_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
     }
 }
 
-// One round for every class of the group, in a single launch (FUSE), or its
-// first two parts (the host then launches rcd_k_steps for parts 3 and 4: with
-// many classes in flight the sweep is bandwidth-bound and the step loop of the
-// class that finishes last would only lengthen it):
-//   1. sweep: every workgroup computes one (class, tile, row chunk) of partial gains
-//   2. the workgroup that completes a tile adds its chunks in order -> gain
-//   3. the workgroup that completes a class runs that class's greedy steps
-//      (while other classes are still being swept)
-//   4. the workgroup that completes the last class writes the next round's plan
-// Completion is detected with arrival counters; nothing ever waits.  Launch r reads plan buffer r&1 and writes
-// the other one.
-// KCAP: no class of the group has more blocks than this (the host picks the
-// smallest instance that fits, which keeps the register count, hence the
-// occupancy, of small-K data sets independent of the K = 16 code).
-template <int KCAP, bool FUSE>
-__global__ void __launch_bounds__(RCD_SWEEP_THREADS)
-rcd_k_round(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int buf)
-{
-    __shared__ float4 lds[RCD_SWEEP_WAVES * 4 * 64];
-    __shared__ StepShared sh;
-    __shared__ int s_flag;
-    const RcdPlan *plan = plans + buf;
-    const int item = blockIdx.x;
-    if (item >= plan->items) return;
-    const int ncls = plans[0].ncls;
-    const int32_t *prefix = plan_prefix(plans, buf);
-    const int c = ncls > 1 ? find_class(prefix, ncls, item) : 0;
-    RcdClass &st = classes[c];
-    const int local = item - prefix[c];
-    const int tiles = (st.nR + RCD_TILE - 1) / RCD_TILE;
-    const int tile = local % tiles;
-    const int chunk = local / tiles;
-    const int nneed = st.nneed;
-    if (nneed <= 1) sweep_body<1>(st, tile, chunk, lds);
-    else if (nneed == 2) sweep_body<2>(st, tile, chunk, lds);
-    else if (nneed == 3) sweep_body<3>(st, tile, chunk, lds);
-    else if (nneed == 4 || KCAP <= 4) sweep_body<4>(st, tile, chunk, lds);
-    else if (nneed <= 6) sweep_body<6>(st, tile, chunk, lds);
-    else if (nneed <= 8 || KCAP <= 8) sweep_body<8>(st, tile, chunk, lds);
-    else if (nneed <= 12) sweep_body<12>(st, tile, chunk, lds);
-    else sweep_body<16>(st, tile, chunk, lds);
+// ---------------------------------------------------------------------------
+// Greedy steps of one class whose similarity is stored (M[v] = candidate v's row),
+// one workgroup of NT threads.  Same loop as class_steps, arranged around trips
+// to memory, of which a call makes three:
+//   1. the class descriptor, copied to LDS;
+//   2. the gain rows of every block that may step (current row, not full): each
+//      thread scans its share of the candidates once and keeps its best per
+//      block, one batched reduction leaves every block's argmax in LDS;
+//      then the loop - argmin block, take that block's argmax, note the position
+//      as removed - runs on LDS alone (if a block's argmax was taken by another
+//      block earlier in the call, its row is scanned again without the removed
+//      positions);
+//   3. the consequences, all contiguous: coverage from the taken candidates' rows
+//      of M, the last list entries (perm and every block's gains) moved into the
+//      holes, the caller's arrays, the descriptor.
+// The gain of a candidate is the sum of its chunk partials, as many as the sweep
+// that built that block's row used.
+// ---------------------------------------------------------------------------
+struct RowsShared {
+    RcdClass d;                                   // the descriptor, then the evolving copy
+    unsigned long long wkey[RCD_KMAX][RCD_STEP_THREADS / 64];
+    int wpos[RCD_KMAX][RCD_STEP_THREADS / 64];
+    unsigned long long bkey[RCD_KMAX];            // argmax of block k's row: (gain bits, ~sample)
+    int bpos[RCD_KMAX];
+    int cand[RCD_KMAX], ncand;                    // blocks that may step in this call
+    int removed[RCD_KMAX], nrem;                  // list positions taken in this call
+    int hole[RCD_KMAX], src[RCD_KMAX], nmove;     // list compaction
+};
 
-    round_tail<RCD_SWEEP_THREADS, RCD_TILE, FUSE>(st, classes, plans, buf, tile, tiles, sh, &s_flag);
+// max over the wave of an unsigned value, same in every lane
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true));
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true));
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true));
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true));
+    const unsigned r0 = __builtin_amdgcn_readlane((int)v, 0), r1 = __builtin_amdgcn_readlane((int)v, 16);
+    const unsigned r2 = __builtin_amdgcn_readlane((int)v, 32), r3 = __builtin_amdgcn_readlane((int)v, 48);
+    return max(max(r0, r1), max(r2, r3));
 }
 
-// Applies what the step loops of the last round decided.  grid = (row blocks, ncls),
-// one thread per row j of the class:
-//   coverage:  cur_js(j) = max(cur_js(j), S(j, v*)) for every step taken
-//   compaction: the column at (dead) position psrc moves to live position ppos
-// All loads come before the stores; sources of moves are dead positions that
-// nothing writes, and the coverage reads use positions as they were before the
-// moves, so the order inside a thread is all that matters.  Row block 0 also
-// moves the gains and perm entries and writes the caller's arrays.
-extern "C" __global__ void __launch_bounds__(256)
-rcd_k_apply(RcdClass *__restrict__ classes, int round_no)
+// wave-wide maximum of a packed key and the position that goes with it
+__device__ __forceinline__ void wave_best(unsigned long long &key, int &pos)
 {
-    RcdClass &st = classes[blockIdx.y];
-    if (st.apply_round != round_no) return;
-    const int nupd = st.nupd, npatch = st.npatch;
-    const int n = st.n, ld = st.ld, K = st.K;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    const gf32 M = (gf32)st.M;
-    if (j < n) {
-        float sv[RCD_KMAX], cv[RCD_KMAX], mv[RCD_KMAX];
-        const gf32 row = M + (size_t)j * ld;
+    const unsigned hi = (unsigned)(key >> 32), lo = (unsigned)key;
+    const unsigned mhi = wave_max_u32(hi);
+    const unsigned mlo = wave_max_u32(hi == mhi ? lo : 0u);
+    const unsigned long long who = __ballot(hi == mhi && lo == mlo);
+    const int src = who ? __ffsll((long long)who) - 1 : 0;
+    pos = __builtin_amdgcn_readlane(pos, src);
+    key = ((unsigned long long)mhi << 32) | mlo;
+}
+
+template <int NT>
+__device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsShared &sh)
+{
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    // ---- trip 1: the descriptor
+    {
+        const gci32 g = (gci32)reinterpret_cast<const int32_t *>(&st);
+        int32_t *l = reinterpret_cast<int32_t *>(&sh.d);
+        for (int i = tid; i < (int)(sizeof(RcdClass) / 4); i += NT) l[i] = g[i];
+    }
+    __syncthreads();
+    RcdClass &d = sh.d;
+    if (d.done) {
+        if (tid == 0) st.nneed = 0;
+        return;
+    }
+    const long long tick0 = wall_clock64();
+    // values that are the same in every lane are kept in scalar registers (uni), so that
+    // addresses are "scalar base + lane offset" and the vector registers stay free for data
+    auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
+    auto uni_ptr = [&](const void *q) {
+        const unsigned long long a = reinterpret_cast<unsigned long long>(q);
+        const unsigned lo = (unsigned)uni((int)(unsigned)a), hi = (unsigned)uni((int)(unsigned)(a >> 32));
+        return ((unsigned long long)hi << 32) | lo;
+    };
+    const int K = uni(d.K), n = uni(d.n), ld = uni(d.ld), total = uni(d.total);
+    const int nR0 = uni(d.nR), t0 = uni(d.t);
+    const size_t cstride = (size_t)K * ld;
+    const gcf32 part = (gcf32)reinterpret_cast<const float *>(uni_ptr(d.part));
+    const gi32 perm = (gi32)reinterpret_cast<int32_t *>(uni_ptr(d.perm));
+    // the sweep that ran since the last call rebuilt these rows
+    if (tid < d.nneed) d.valid[d.need[tid]] = 1;
+    __syncthreads();
+    if (tid == 0) {
+        int m = 0;
+        for (int k = 0; k < K; ++k)
+            if (d.valid[k] && d.cnt[k] < d.cap[k]) sh.cand[m++] = k;
+        sh.ncand = m;
+        sh.nrem = 0;
+        sh.nmove = 0;
+    }
+    __syncthreads();
+    const int ncand = uni(sh.ncand);
+
+    // ---- trip 2: every candidate block's argmax
+    // scan of block k's row over the list positions not in removed[0 .. nrem)
+    auto scan_row = [&](int k, int nrem, unsigned long long &best, int &bpos) {
+        const gcf32 g = part + (size_t)k * ld;
+        const int nchunk = uni(d.cblk[k]);
+        constexpr int UA = 8;
+        for (int p0 = 0; p0 < nR0; p0 += UA * NT) {
+            float gv[UA];
+            int pv[UA];
 #pragma unroll
-        for (int i = 0; i < RCD_KMAX; ++i)
-            if (i < nupd) {
-                sv[i] = row[st.usrc[i]];
-                cv[i] = ((gf32)st.cur)[(size_t)st.ujs[i] * ld + j];
+            for (int u = 0; u < UA; ++u) {
+                const int p = p0 + u * NT + tid;
+                if (p < nR0) {
+                    gv[u] = g[p];
+                    pv[u] = perm[p];
+                }
+            }
+            for (int c = 1; c < nchunk; ++c)
+#pragma unroll
+                for (int u = 0; u < UA; ++u) {
+                    const int p = p0 + u * NT + tid;
+                    if (p < nR0) gv[u] += g[c * cstride + p];
+                }
+#pragma unroll
+            for (int u = 0; u < UA; ++u) {
+                const int p = p0 + u * NT + tid;
+                if (p < nR0) {
+                    bool gone = false;
+                    for (int i = 0; i < nrem; ++i) gone |= sh.removed[i] == p;
+                    const unsigned long long key = pack_key(gv[u], pv[u]);
+                    if (!gone && key > best) { best = key; bpos = p; }
+                }
+            }
+        }
+    };
+    // KC candidate blocks at once, from the i0-th on: KC x UB gains in flight per thread
+    auto scan_all = [&](auto kc_tag, auto ub_tag, int i0) {
+        constexpr int KC = decltype(kc_tag)::value, UB = decltype(ub_tag)::value;
+        const int ncand = uni(sh.ncand) - i0;
+        unsigned long long best[KC];
+        int bpos[KC], kk[KC], nc[KC];
+#pragma unroll
+        for (int i = 0; i < KC; ++i) {
+            best[i] = 0ull;
+            bpos[i] = -1;
+            kk[i] = uni(sh.cand[i < ncand ? i0 + i : 0]);
+            nc[i] = uni(d.cblk[kk[i]]);
+        }
+        int ncmax = 1;
+#pragma unroll
+        for (int i = 0; i < KC; ++i) ncmax = max(ncmax, i < ncand ? nc[i] : 1);
+        for (int p0 = 0; p0 < nR0; p0 += UB * NT) {
+            float gv[KC][UB];
+            int pv[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int p = p0 + u * NT + tid;
+                if (p < nR0) {
+                    pv[u] = perm[p];
+#pragma unroll
+                    for (int i = 0; i < KC; ++i)
+                        if (i < ncand) gv[i][u] = part[(size_t)kk[i] * ld + p];
+                }
+            }
+            // further chunk partials, if any block's row has them: kept out of the way of the
+            // loads above, which must all be in flight together
+            if (ncmax > 1) {
+                for (int c = 1; c < ncmax; ++c)
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) {
+                        const int p = p0 + u * NT + tid;
+#pragma unroll
+                        for (int i = 0; i < KC; ++i)
+                            if (p < nR0 && i < ncand && c < nc[i]) gv[i][u] += part[c * cstride + (size_t)kk[i] * ld + p];
+                    }
             }
 #pragma unroll
-        for (int i = 0; i < RCD_KMAX; ++i)
-            if (i < npatch) mv[i] = row[st.psrc[i]];
+            for (int u = 0; u < UB; ++u) {
+                const int p = p0 + u * NT + tid;
+                if (p < nR0) {
 #pragma unroll
-        for (int i = 0; i < RCD_KMAX; ++i)
-            if (i < nupd && sv[i] > cv[i]) ((gf32)st.cur)[(size_t)st.ujs[i] * ld + j] = sv[i];
-#pragma unroll
-        for (int i = 0; i < RCD_KMAX; ++i)
-            if (i < npatch) row[st.ppos[i]] = mv[i];
-    }
-    if (blockIdx.x == 0) {
-        const int tid = threadIdx.x;
-        for (int e = tid; e < npatch * (K + 1); e += 256) {
-            const int i = e / (K + 1), k = e % (K + 1);
-            const int dpos = st.ppos[i], spos = st.psrc[i];
-            if (k < K) st.gain[(size_t)k * ld + dpos] = st.gain[(size_t)k * ld + spos];
-            else st.perm[dpos] = st.perm[spos];
+                    for (int i = 0; i < KC; ++i)
+                        if (i < ncand) {
+                            const unsigned long long key = pack_key(gv[i][u], pv[u]);
+                            if (key > best[i]) { best[i] = key; bpos[i] = p; }
+                        }
+                }
+            }
         }
+#pragma unroll
+        for (int i = 0; i < KC; ++i)
+            if (i < ncand) {
+                wave_best(best[i], bpos[i]);
+                if (lane == 0) { sh.wkey[i0 + i][wave] = best[i]; sh.wpos[i0 + i][wave] = bpos[i]; }
+            }
+    };
+    if (K <= 4) {
+        if (ncand > 0) scan_all(std::integral_constant<int, 4>{}, std::integral_constant<int, 8>{}, 0);
+    } else {
+        for (int i0 = 0; i0 < ncand; i0 += 8) scan_all(std::integral_constant<int, 8>{}, std::integral_constant<int, 4>{}, i0);
+    }
+    __syncthreads();
+    if (tid < ncand) {
+        unsigned long long best = sh.wkey[tid][0];
+        int bpos = sh.wpos[tid][0];
+        for (int w = 1; w < NW; ++w)
+            if (sh.wkey[tid][w] > best) { best = sh.wkey[tid][w]; bpos = sh.wpos[tid][w]; }
+        sh.bkey[sh.cand[tid]] = best;
+        sh.bpos[sh.cand[tid]] = bpos;
+    }
+    __syncthreads();
+
+    // ---- the loop (Algorithm 1's while body), on LDS
+    int nR = nR0, t = t0, done = 0;
+    long long useful = 0;
+    for (;;) {
+        if (t >= total) { done = 1; break; }
+        int js = -1;
+        double fbest = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (d.cnt[k] >= d.cap[k]) continue;
+            const double fk = d.f[k];
+            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
+        }
+        if (js < 0) { done = 1; break; }
+        js = uni(js);
+        if (!d.valid[js]) break;
+        const int nrem = uni(sh.nrem);
+        int pstar = sh.bpos[js];
+        bool taken = false;
+        for (int i = 0; i < nrem; ++i) taken |= sh.removed[i] == pstar;
+        if (taken) {
+            // another block took this block's best candidate earlier in the call
+            unsigned long long best = 0ull;
+            int bpos = -1;
+            scan_row(js, nrem, best, bpos);
+            wave_best(best, bpos);
+            __syncthreads();   // everyone is past reading bkey/bpos/wkey of the previous step
+            if (lane == 0) { sh.wkey[0][wave] = best; sh.wpos[0][wave] = bpos; }
+            __syncthreads();
+            if (tid == 0) {
+                best = sh.wkey[0][0];
+                bpos = sh.wpos[0][0];
+                for (int w = 1; w < NW; ++w)
+                    if (sh.wkey[0][w] > best) { best = sh.wkey[0][w]; bpos = sh.wpos[0][w]; }
+                sh.bkey[js] = best;
+                sh.bpos[js] = bpos;
+            }
+            __syncthreads();
+            pstar = sh.bpos[js];
+        }
+        const unsigned long long key = sh.bkey[js];
+        const float gbest = __uint_as_float((unsigned)(key >> 32));
+        const int vstar = (int)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
+        __syncthreads();   // everyone has read the state this step was decided on
+        if (tid == 0) {
+            const int u = sh.nrem;
+            sh.removed[u] = pstar;
+            sh.nrem = u + 1;
+            d.ujs[u] = js; d.uv[u] = vstar; d.ut[u] = t;
+            d.cnt[js] += 1;
+            d.f[js] += (double)gbest;
+            d.valid[js] = 0;
+        }
+        useful += nR;
+        nR -= 1;
+        ++t;
+        __syncthreads();
+    }
+
+    // ---- trip 3: consequences
+    const int nupd = uni(sh.nrem);
+    if (tid == 0) {
+        // holes: removed positions below the new length; sources: surviving positions at or above it
+        int nm = 0, s = nR;
+        for (int i = 0; i < nupd; ++i) {
+            const int h = sh.removed[i];
+            if (h >= nR) continue;
+            for (;; ++s) {
+                bool gone = false;
+                for (int q = 0; q < nupd; ++q) gone |= sh.removed[q] == s;
+                if (!gone) break;
+            }
+            sh.hole[nm] = h;
+            sh.src[nm] = s++;
+            ++nm;
+        }
+        sh.nmove = nm;
+    }
+    __syncthreads();
+    const int nmove = uni(sh.nmove);
+    {
+        // coverage: cur_js(j) = max(cur_js(j), S(j, v*)); a block steps at most once per call,
+        // so the updates touch different vectors and all loads can precede all stores
+        const gcf32 M = (gcf32)reinterpret_cast<const float *>(uni_ptr(d.M));
+        const gf32 cur = (gf32)reinterpret_cast<float *>(uni_ptr(d.cur));
+        // two pieces of each vector per thread and trip: a class of up to 8192 samples needs one
+        for (int u0 = 0; u0 < nupd; u0 += 4)
+            for (int j0 = tid * 4; j0 < ld; j0 += NT * 8) {
+                const int j1 = j0 + NT * 4;
+                f32x4 m[2][4], c[2][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (u0 + u < nupd) {
+                        const gcf32 mr = M + (size_t)uni(d.uv[u0 + u]) * ld;
+                        const gcf32 cr = cur + (size_t)uni(d.ujs[u0 + u]) * ld;
+                        m[0][u] = *(gcf32x4)(mr + j0);
+                        c[0][u] = *(gcf32x4)(cr + j0);
+                        if (j1 < ld) {
+                            m[1][u] = *(gcf32x4)(mr + j1);
+                            c[1][u] = *(gcf32x4)(cr + j1);
+                        }
+                    }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (u0 + u < nupd) {
+                        const gf32 cr = cur + (size_t)uni(d.ujs[u0 + u]) * ld;
+                        f32x4 r;
+                        r.x = fmaxf(c[0][u].x, m[0][u].x); r.y = fmaxf(c[0][u].y, m[0][u].y);
+                        r.z = fmaxf(c[0][u].z, m[0][u].z); r.w = fmaxf(c[0][u].w, m[0][u].w);
+                        *(gf32x4)(cr + j0) = r;
+                        if (j1 < ld) {
+                            r.x = fmaxf(c[1][u].x, m[1][u].x); r.y = fmaxf(c[1][u].y, m[1][u].y);
+                            r.z = fmaxf(c[1][u].z, m[1][u].z); r.w = fmaxf(c[1][u].w, m[1][u].w);
+                            *(gf32x4)(cr + j1) = r;
+                        }
+                    }
+            }
+        // list compaction: perm and every block's partial gains
+        int cmax = 1;
+        for (int k = 0; k < K; ++k) cmax = max(cmax, d.cblk[k]);
+        const gf32 wpart = (gf32)reinterpret_cast<float *>(uni_ptr(d.part));
+        for (int e = tid; e < nmove * K * cmax; e += NT) {
+            const int i = e / (K * cmax), r = e % (K * cmax);   // r = chunk * K + block
+            if (r / K < d.cblk[r % K]) wpart[(size_t)r * ld + sh.hole[i]] = wpart[(size_t)r * ld + sh.src[i]];
+        }
+        if (tid < nmove) perm[sh.hole[tid]] = perm[sh.src[tid]];
         if (tid < nupd) {
-            const int v = st.uv[tid];
-            const int oi = st.out_index ? st.out_index[v] : v;
-            st.assign_out[oi] = st.ujs[tid];
-            if (st.order_out) st.order_out[oi] = st.ut[tid];
+            const int v = d.uv[tid];
+            const int oi = d.out_index ? d.out_index[v] : v;
+            d.assign_out[oi] = d.ujs[tid];
+            if (d.order_out) d.order_out[oi] = d.ut[tid];
         }
     }
+    // ---- the descriptor: what the next sweep must do, the state, the counters
+    if (tid == 0) {
+        int nneed = 0;
+        if (!done)
+            for (int k = 0; k < K; ++k)
+                if (d.cnt[k] < d.cap[k] && !d.valid[k]) d.need[nneed++] = k;
+        d.nneed = nneed;
+        if (nneed > 0) {
+            // the coverage vectors of the evaluated blocks share the sweep workgroup's LDS:
+            // the more blocks, the shorter the chunk of j one pass covers
+            int jc = (RCD_SWEEP_LDS_FLOATS / nneed) / 256 * 256;
+            jc = jc > ld ? ld : jc;
+            const int C = (ld + jc - 1) / jc;
+            d.rpc = jc;
+            d.C = C;
+            for (int i = 0; i < nneed; ++i) d.cblk[d.need[i]] = C;
+            d.stat_sweeps += 1;
+            d.stat_entries += (long long)nR * n;
+            d.stat_computed += (long long)nneed * nR;
+        }
+        d.stat_steps += t - t0;
+        d.stat_useful += useful;
+        d.nupd = nupd;
+        d.npatch = nmove;
+        d.apply_round += 1;
+        d.nR = nR;
+        d.t = t;
+        d.done = done;
+        d.stat_ticks += wall_clock64() - tick0;
+        if (done) __hip_atomic_fetch_add(&plans[0].ndone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    {
+        // everything from nR on changes; the fixed part in front of it stays as it is
+        constexpr int first = (int)(offsetof(RcdClass, nR) / 4);
+        gi32 g = (gi32)reinterpret_cast<int32_t *>(&st);
+        const int32_t *l = reinterpret_cast<const int32_t *>(&sh.d);
+        for (int i = first + tid; i < (int)(sizeof(RcdClass) / 4); i += NT) g[i] = l[i];
+    }
+}
+
+// Stored similarity: one workgroup per class runs the class's steps; a round is
+// the sweep launch and this one.  plans[0].ndone counts the finished classes.
+extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
+rcd_k_steps_rows(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
+{
+    __shared__ RowsShared sh;
+    steps_rows<RCD_STEP_THREADS>(classes[blockIdx.x], plans, sh);
+}
+
+// Gain sweep of every class of a stored-similarity group.  The workgroups are dealt
+// to the classes once, in proportion to their size (wgmap[b] = class, index among
+// the class's workgroups, their count): a workgroup stays with one class, stages that
+// class's coverage vectors once per pass and then only streams rows.
+extern "C" __global__ void __launch_bounds__(RCD_SWEEP_THREADS)
+rcd_k_sweep_rows(const RcdClass *__restrict__ classes, const RcdWg *__restrict__ wgmap)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds_cur[];
+    const RcdWg wg = wgmap[blockIdx.x];
+    const RcdClass &st = classes[wg.cls];
+    const int nneed = st.nneed;
+    if (nneed <= 0 || st.done) return;
+    if (nneed == 1) sweep_rows<1>(st, wg.w, wg.W, lds_cur);
+    else if (nneed == 2) sweep_rows<2>(st, wg.w, wg.W, lds_cur);
+    else if (nneed == 3) sweep_rows<3>(st, wg.w, wg.W, lds_cur);
+    else if (nneed == 4) sweep_rows<4>(st, wg.w, wg.W, lds_cur);
+    else if (nneed <= 6) sweep_rows<6>(st, wg.w, wg.W, lds_cur);
+    else if (nneed <= 8) sweep_rows<8>(st, wg.w, wg.W, lds_cur);
+    else if (nneed <= 12) sweep_rows<12>(st, wg.w, wg.W, lds_cur);
+    else sweep_rows<16>(st, wg.w, wg.W, lds_cur);
 }
 
 // Initial state of a group of classes: cur = 0 (f of the empty set is 0),
@@ -638,7 +991,7 @@ extern "C" __global__ void rcd_k_init(const RcdClass *__restrict__ classes)
     for (size_t i = i0; i < ncur; i += stride) st.cur[i] = 0.f;
     for (int i = i0; i < st.ld; i += stride) st.perm[i] = i;
     for (int i = i0; i < st.ld / RCD_TILE_RC; i += stride) st.tilecnt[i] = 0;
-    for (int i = i0; i < st.n; i += stride) {
+    for (int i = i0; i < st.n && st.assign_out; i += stride) {
         const int oi = st.out_index ? st.out_index[i] : i;
         st.assign_out[oi] = -1;
         if (st.order_out) st.order_out[oi] = -1;
@@ -665,24 +1018,31 @@ rcd_k_objective(const RcdClass *__restrict__ classes, double *__restrict__ obj, 
     if (threadIdx.x == 0) obj[(size_t)blockIdx.y * Kstride + k] = sh[0];
 }
 
-// Copy a caller's S (n x n, pitch lds) into the working matrix (pitch ld) and
-// flag entries outside [0,1] or NaN.  grid-stride over rows.
+// Copy a caller's S (n x n, pitch lds) transposed into the working matrix (pitch ld):
+// M[v][j] = S[j][v], so that candidate v's similarities to every j are one contiguous
+// row whether or not S is symmetric; zero the pad columns; flag entries outside [0,1]
+// or NaN.  grid = (ld/32, ceil(n/32)), 32 x 8 threads, one 32 x 32 tile through LDS.
 extern "C" __global__ void __launch_bounds__(256)
 rcd_k_copy_check(const float *__restrict__ S, long long lds, float *__restrict__ M, int ld, int n,
                  RcdPlan *plan)
 {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int jb = blockIdx.x * 32, vb = blockIdx.y * 32;
     int bad = 0;
-    for (int j = blockIdx.x; j < n; j += gridDim.x) {
-        const float *src = S + (size_t)j * lds;
-        float *dst = M + (size_t)j * ld;
-        for (int p = threadIdx.x; p < ld; p += 256) {
-            float v = 0.f;
-            if (p < n) {
-                v = src[p];
-                if (!(v >= 0.f && v <= 1.f)) bad = 1;
-            }
-            dst[p] = v;
+    for (int r = ty; r < 32; r += 8) {
+        const int j = jb + r, v = vb + tx;
+        float x = 0.f;
+        if (j < n && v < n) {
+            x = S[(size_t)j * lds + v];
+            if (!(x >= 0.f && x <= 1.f)) bad = 1;
         }
+        tile[r][tx] = x;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int v = vb + r, j = jb + tx;
+        if (v < n && j < ld) M[(size_t)v * ld + j] = tile[tx][r];
     }
     if (bad) plan->bad = 1;
 }
@@ -693,7 +1053,11 @@ extern "C" __global__ void rcd_k_export_gains(const RcdClass *__restrict__ class
     const RcdClass &st = classes[0];
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
     const int k = blockIdx.y;
-    if (v < st.n) out[(size_t)k * st.n + v] = st.gain[(size_t)k * st.ld + v];
+    if (v < st.n) {
+        float g = 0.f;
+        for (int c = 0; c < st.C; ++c) g += st.part[((size_t)c * st.K + k) * st.ld + v];
+        out[(size_t)k * st.n + v] = g;
+    }
 }
 
 extern "C" __global__ void rcd_k_import_cur(const RcdClass *__restrict__ classes, const float *__restrict__ in)

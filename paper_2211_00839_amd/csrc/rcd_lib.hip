@@ -94,9 +94,13 @@ constexpr int RCD_SLOTS = 4;
 
 size_t plan_area_bytes(int ncls) { return up256(2 * sizeof(RcdPlan) + 2 * (size_t)(ncls + 1) * 4); }
 
+// Room for a lane's workgroup-to-class table of the stored-S sweep.
+constexpr int RCD_MAX_SWEEP_WGS = 2048;
+size_t wg_area_bytes(int ncls) { return up256((size_t)(RCD_MAX_SWEEP_WGS + ncls) * sizeof(RcdWg)); }
+
 size_t group_fixed_bytes(int ncls, int K)
 {
-    return up256((size_t)ncls * sizeof(RcdClass)) + RCD_MAX_LANES * plan_area_bytes(ncls) +
+    return up256((size_t)ncls * sizeof(RcdClass)) + RCD_MAX_LANES * (plan_area_bytes(ncls) + wg_area_bytes(ncls)) +
            up256((size_t)ncls * K * sizeof(double));
 }
 
@@ -104,6 +108,8 @@ struct Group {
     RcdClass *classes_dev = nullptr;
     RcdPlan *plan_dev = nullptr;                 // = plan_area[0]
     RcdPlan *plan_area[RCD_MAX_LANES] = {};      // one plan record per lane (only the owner of the workspace slice has them all)
+    RcdWg *wgmap_dev = nullptr;                  // = wg_area[0]
+    RcdWg *wg_area[RCD_MAX_LANES] = {};
     double *obj_dev = nullptr;
     std::vector<RcdClass> host;   // kept alive until the stream has consumed it
     int K = 0;
@@ -120,7 +126,7 @@ bool carve_class(Carver &cv, RcdClass &c, int64_t n, int K, const int64_t *cap, 
     if (stored) c.M = cv.take<float>((size_t)n * ld);
     else c.sq = cv.take<float>((size_t)n);
     c.tw = stored ? RCD_TILE : RCD_TILE_RC;
-    c.row_align = stored ? RCD_ROW_ALIGN : RCD_ROWS_RC;
+    c.row_align = RCD_ROWS_RC;
     c.cur = cv.take<float>((size_t)K * ld);
     c.part = cv.take<float>((size_t)RCD_CMAX * K * ld);
     c.gain = cv.take<float>((size_t)K * ld);
@@ -143,15 +149,59 @@ int sweep_items_bound(const RcdClass &c)
     return std::min(RCD_CMAX * tiles0, c.target_items + tiles0);
 }
 
-void choose_chunks(int n, int nR, int target_items, int *C, int *rpc)
+// Stored-S sweep evaluating nneed blocks: length of a chunk of j and number of chunks
+// (the step loop applies the same rule on the device).
+void stored_chunks(int ld, int nneed, int *C, int *jc)
 {
-    const int tiles = (nR + RCD_TILE - 1) / RCD_TILE;
-    int c = (target_items + tiles - 1) / tiles;
-    c = c < 1 ? 1 : (c > RCD_CMAX ? RCD_CMAX : c);
-    int r = (n + c - 1) / c;
-    r = (r + RCD_ROW_ALIGN - 1) & ~(RCD_ROW_ALIGN - 1);
-    *rpc = r;
-    *C = (n + r - 1) / r;
+    int len = (RCD_SWEEP_LDS_FLOATS / std::max(nneed, 1)) / 256 * 256;
+    len = std::min(len, ld);
+    *jc = len;
+    *C = (ld + len - 1) / len;
+}
+
+// Can a class of n samples and K blocks run in stored mode (chunk partials fit their buffer)?
+bool stored_supported(int64_t n, int K)
+{
+    int C, jc;
+    stored_chunks(pitch_of(n), K, &C, &jc);
+    return C <= RCD_CMAX;
+}
+
+// Deal `total` sweep workgroups to the classes in proportion to their matrix sizes,
+// at least one each.  Returns the table (class-major).
+std::vector<RcdWg> deal_workgroups(const std::vector<RcdClass> &cls, int total)
+{
+    double sum = 0.0;
+    for (const RcdClass &c : cls) sum += (double)c.n * c.n;
+    std::vector<RcdWg> map;
+    const int ncls = (int)cls.size();
+    for (int i = 0; i < ncls; ++i) {
+        const double share = sum > 0.0 ? (double)cls[i].n * cls[i].n / sum : 1.0 / ncls;
+        int W = (int)std::lround(share * total);
+        // no more workgroups than rows for their waves to take
+        W = std::min(W, (cls[i].n + RCD_SWEEP_WAVES - 1) / RCD_SWEEP_WAVES);
+        W = std::max(W, 1);
+        for (int w = 0; w < W && (int)map.size() < RCD_MAX_SWEEP_WGS + i; ++w) map.push_back(RcdWg{i, w, W, 0});
+    }
+    // a class cut short by the table's capacity: its workgroups must know the real count
+    std::vector<int> have(ncls, 0);
+    for (const RcdWg &m : map) have[m.cls] += 1;
+    for (RcdWg &m : map) m.W = have[m.cls];
+    return map;
+}
+
+int g_cu_count = 0;
+int sweep_setup()
+{
+    if (g_cu_count == 0) {
+        int dev = 0, cus = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rcd_k_sweep_rows),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, RCD_SWEEP_LDS_FLOATS * 4));
+        g_cu_count = std::max(cus, 1);
+    }
+    return RCD_OK;
 }
 
 int ensure_pinned()
@@ -185,8 +235,8 @@ struct Lane {
     bool recompute = false, fused = false, prof = false, finished = false;
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
     void (*apply_rc)(RcdClass *, int) = nullptr;
-    void (*round_st)(RcdClass *, RcdPlan *, int) = nullptr;
-    dim3 apply_grid, apply_rc_grid;
+    int sweep_wgs = 0;       // stored S: workgroups of the sweep launch
+    dim3 apply_rc_grid;
     hipEvent_t ev[RCD_SLOTS] = {};
     int64_t launches = 0, max_batches = 0;
     int64_t batch = 0;       // batches enqueued
@@ -197,8 +247,8 @@ struct Lane {
 
     void launch_apply(int rn)
     {
+        // stored S: the step loops apply their own decisions
         if (recompute) hipLaunchKernelGGL(apply_rc, apply_rc_grid, dim3(256), 0, stream, g->classes_dev, rn);
-        else hipLaunchKernelGGL(rcd_k_apply, apply_grid, dim3(256), 0, stream, g->classes_dev, rn);
     }
 
     void read_events(int64_t b)
@@ -215,7 +265,8 @@ struct Lane {
 
     // Upload the descriptors, reset the state, run the first step loop.
     // target_total: sweep workgroups per round this lane aims at.
-    int start(Group &group, hipStream_t s, int slot_, int target_total, bool profile)
+    // sweep_target: workgroups the stored-S sweep launch aims at.
+    int start(Group &group, hipStream_t s, int slot_, int target_total, int sweep_target, bool profile)
     {
         g = &group;
         stream = s;
@@ -244,21 +295,31 @@ struct Lane {
         HIP_TRY(hipMemcpyAsync(&g->plan_dev[1], &plan0, sizeof plan0, hipMemcpyHostToDevice, stream));
         HIP_TRY(hipMemcpyAsync(g->classes_dev, g->host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
         hipLaunchKernelGGL(rcd_k_init, dim3(64, ncls), dim3(256), 0, stream, g->classes_dev);
-        apply_grid = dim3((unsigned)((max_n + 255) / 256), (unsigned)ncls);
         apply_rc_grid = dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls);
-        // step loop number 1 (the bootstrap) and its apply; step loop r+2 runs inside round r
-        hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev);
-
-        for (int i = 0; i < RCD_SLOTS; ++i) HIP_TRY(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
         // a group is homogeneous: all stored, or all recomputed from the same X
         const RcdClass &first = g->host[0];
         recompute = first.mode == RCD_MODE_RECOMPUTE;
+        if (!recompute) {
+            RCD_TRY(sweep_setup());
+            const std::vector<RcdWg> map = deal_workgroups(g->host, std::min(sweep_target, RCD_MAX_SWEEP_WGS));
+            sweep_wgs = (int)map.size();
+            // pageable source: the copy is staged before the call returns
+            HIP_TRY(hipMemcpyAsync(g->wgmap_dev, map.data(), sizeof(RcdWg) * map.size(), hipMemcpyHostToDevice, stream));
+        }
+        // step loop number 1 (the bootstrap) and its apply; step loop r+2 follows round r's sweep
+        if (recompute)
+            hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev);
+        else
+            hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                               g->plan_dev);
+
+        for (int i = 0; i < RCD_SLOTS; ++i) HIP_TRY(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
         const int esz = first.dt == RCD_F32 ? 4 : 2;
         const bool fast = recompute && (reinterpret_cast<uintptr_t>(first.X) & 15) == 0 &&
                           ((first.ldx64 * esz) % 16) == 0 && ((int64_t)first.d * esz) % sim::ROWB == 0;
         // One launch per round (sweep + step loops fused) pays off when few classes are in
         // flight; with many, the sweep is bandwidth-bound and the step loops get their own launch.
-        fused = env_int("RCD_FUSED", ncls <= 2 ? 1 : 0, 0, 1) != 0;
+        fused = recompute && env_int("RCD_FUSED", ncls <= 2 ? 1 : 0, 0, 1) != 0;
         if (recompute) {
             if (first.dt == RCD_F32) {
                 round_rc = fused ? (fast ? rcd_k_round_rc<float, true, true> : rcd_k_round_rc<float, false, true>)
@@ -270,9 +331,6 @@ struct Lane {
                 apply_rc = rcd_k_apply_rc<__bf16>;
             }
         }
-        const int K = g->K;
-        round_st = fused ? (K <= 4 ? rcd_k_round<4, true> : (K <= 8 ? rcd_k_round<8, true> : rcd_k_round<16, true>))
-                         : (K <= 4 ? rcd_k_round<4, false> : (K <= 8 ? rcd_k_round<8, false> : rcd_k_round<16, false>));
         launches = 3;
         round_no = 0;
         launch_apply(1);
@@ -306,18 +364,22 @@ struct Lane {
             if (recompute)
                 hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), 0, stream, g->classes_dev, g->plan_dev, buf);
             else
-                hipLaunchKernelGGL(round_st, dim3(items_ub), dim3(RCD_SWEEP_THREADS), 0, stream, g->classes_dev,
-                                   g->plan_dev, buf);
+                hipLaunchKernelGGL(rcd_k_sweep_rows, dim3(sweep_wgs), dim3(RCD_SWEEP_THREADS),
+                                   RCD_SWEEP_LDS_FLOATS * 4, stream, (const RcdClass *)g->classes_dev,
+                                   (const RcdWg *)g->wgmap_dev);
             ++round_no;
             if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
-            if (!fused)
+            if (!recompute)
+                hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                                   g->plan_dev);
+            else if (!fused)
                 hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                    g->plan_dev);
             if (pe) (void)hipEventRecord((*pe)[3 * r + 2], stream);
             launch_apply(round_no + 1);
             if (pe) (void)hipEventRecord((*pe)[3 * r + 3], stream);
         }
-        launches += (fused ? 2 : 3) * (int64_t)rounds;
+        launches += (!recompute || fused ? 2 : 3) * (int64_t)rounds;
         hipError_t le = hipGetLastError();
         if (le != hipSuccess) {
             snprintf(g_hip_err, sizeof g_hip_err, "kernel launch -> %s", hipGetErrorString(le));
@@ -402,11 +464,15 @@ int run_groups(std::vector<Group> &groups, hipStream_t stream)
     if (nl > RCD_MAX_LANES) return RCD_ERR_INVALID_ARG;
     RCD_TRY(ensure_pinned());
     const int target_total = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
+    RCD_TRY(sweep_setup());
+    // one workgroup of the stored-S sweep fills a compute unit (its LDS holds the coverage vectors);
+    // two per unit, run one after the other, even out what the waves of the first leave uneven
+    const int sweep_target = env_int("RCD_SWEEP_WGS", 2 * g_cu_count, 1, RCD_MAX_SWEEP_WGS);
     std::vector<Lane> lanes(nl);
     int rc = RCD_OK;
     int started = 0;
     if (nl == 1) {
-        rc = lanes[0].start(groups[0], stream, 0, target_total, g_profile_on != 0);
+        rc = lanes[0].start(groups[0], stream, 0, target_total, sweep_target, g_profile_on != 0);
         started = 1;
     } else {
         RCD_TRY(ensure_side_streams(nl));
@@ -421,7 +487,7 @@ int run_groups(std::vector<Group> &groups, hipStream_t stream)
         }
         const int per_lane = std::max(256, target_total * 2 / (nl + 1));
         for (int i = 0; i < nl && rc == RCD_OK; ++i) {
-            rc = lanes[i].start(groups[i], g_side[i], i, per_lane, false);
+            rc = lanes[i].start(groups[i], g_side[i], i, per_lane, sweep_target, false);
             ++started;
         }
     }
@@ -469,6 +535,9 @@ bool carve_group_fixed(Carver &cv, Group &g, int ncls, int K)
     for (int i = 0; i < RCD_MAX_LANES; ++i)
         g.plan_area[i] = reinterpret_cast<RcdPlan *>(cv.take<char>(plan_area_bytes(ncls)));
     g.plan_dev = g.plan_area[0];
+    for (int i = 0; i < RCD_MAX_LANES; ++i)
+        g.wg_area[i] = reinterpret_cast<RcdWg *>(cv.take<char>(wg_area_bytes(ncls)));
+    g.wgmap_dev = g.wg_area[0];
     g.obj_dev = cv.take<double>((size_t)ncls * K);
     g.K = K;
     return !cv.fail;
@@ -654,6 +723,7 @@ int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const flo
     RCD_TRY(check_common(n, K));
     if (n == 0) return RCD_OK;
     if (!S_dev || !cur_dev || !gains_dev || ld_s < n) return RCD_ERR_INVALID_ARG;
+    if (!stored_supported(n, K)) return RCD_ERR_UNSUPPORTED;
     RCD_TRY(check_workspace(workspace_dev, workspace_bytes, rcd_class_workspace_bytes(n, K, RCD_MODE_STORED)));
     Carver cv(workspace_dev, workspace_bytes);
     Group g;
@@ -665,28 +735,23 @@ int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const flo
     c.assign_out = nullptr;
     c.nneed = K;
     for (int k = 0; k < K; ++k) c.need[k] = k;
-    c.target_items = env_int("RCD_TARGET_ITEMS", 2048, 1, 1 << 20);
-    choose_chunks(c.n, c.nR, c.target_items, &c.C, &c.rpc);
-    const int tiles = (c.n + RCD_TILE - 1) / RCD_TILE;
-    struct { RcdPlan p[2]; int32_t pre[4]; } plan;
-    memset(&plan, 0, sizeof plan);
-    plan.p[0].ncls = plan.p[1].ncls = 1;
-    plan.p[0].items = tiles * c.C;
-    plan.p[0].nactive = 1;
-    plan.pre[0] = 0; plan.pre[1] = plan.p[0].items;
-    HIP_TRY(hipMemcpyAsync(g.plan_dev, &plan, sizeof plan, hipMemcpyHostToDevice, stream));
+    stored_chunks(c.ld, K, &c.C, &c.rpc);
+    RCD_TRY(sweep_setup());
+    const std::vector<RcdWg> map =
+        deal_workgroups(g.host, env_int("RCD_SWEEP_WGS", 2 * g_cu_count, 1, RCD_MAX_SWEEP_WGS));
+    RcdPlan plan[2];
+    memset(plan, 0, sizeof plan);
+    plan[0].ncls = plan[1].ncls = 1;
+    HIP_TRY(hipMemcpyAsync(g.plan_dev, plan, sizeof plan, hipMemcpyHostToDevice, stream));
     HIP_TRY(hipMemcpyAsync(g.classes_dev, g.host.data(), sizeof(RcdClass), hipMemcpyHostToDevice, stream));
-    hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
-                       (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
+    HIP_TRY(hipMemcpyAsync(g.wgmap_dev, map.data(), sizeof(RcdWg) * map.size(), hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(rcd_k_copy_check, dim3((unsigned)(c.ld / 32), (unsigned)((n + 31) / 32)), dim3(256), 0, stream,
+                       S_dev, (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
+    hipLaunchKernelGGL(rcd_k_init, dim3(64, 1), dim3(256), 0, stream, (const RcdClass *)g.classes_dev);
     hipLaunchKernelGGL(rcd_k_import_cur, dim3((unsigned)((n + 255) / 256), K), dim3(256), 0, stream,
                        (const RcdClass *)g.classes_dev, cur_dev);
-    HIP_TRY(hipMemsetAsync(c.tilecnt, 0, (size_t)(c.ld / RCD_TILE) * 4, stream));
-    // total = 0: after the sweep the class's step loop finds nothing to do
-    void (*sweep_kernel)(RcdClass *, RcdPlan *, int) = rcd_k_round<16, true>;
-    if (K <= 4) sweep_kernel = rcd_k_round<4, true>;
-    else if (K <= 8) sweep_kernel = rcd_k_round<8, true>;
-    hipLaunchKernelGGL(sweep_kernel, dim3(plan.p[0].items), dim3(RCD_SWEEP_THREADS), 0, stream, g.classes_dev,
-                       g.plan_dev, 0);
+    hipLaunchKernelGGL(rcd_k_sweep_rows, dim3((unsigned)map.size()), dim3(RCD_SWEEP_THREADS), RCD_SWEEP_LDS_FLOATS * 4,
+                       stream, (const RcdClass *)g.classes_dev, (const RcdWg *)g.wgmap_dev);
     hipLaunchKernelGGL(rcd_k_export_gains, dim3((unsigned)((n + 255) / 256), K), dim3(256), 0, stream,
                        (const RcdClass *)g.classes_dev, gains_dev);
     HIP_TRY(hipGetLastError());
@@ -719,6 +784,7 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     const bool stored = S_dev != nullptr;
     if (stored) {
         if (ld_s < n) return RCD_ERR_INVALID_ARG;
+        if (!stored_supported(n, K)) return RCD_ERR_UNSUPPORTED;
     } else {
         if (!X_dev || d < 1 || ld_x < d || !(sigma2 > 0.f)) return RCD_ERR_INVALID_ARG;
         if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
@@ -736,8 +802,8 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     c.order_out = order_dev;
     HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
     if (stored) {
-        hipLaunchKernelGGL(rcd_k_copy_check, dim3(std::min<int64_t>(n, 4096)), dim3(256), 0, stream, S_dev,
-                           (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
+        hipLaunchKernelGGL(rcd_k_copy_check, dim3((unsigned)(c.ld / 32), (unsigned)((n + 31) / 32)), dim3(256), 0,
+                           stream, S_dev, (long long)ld_s, c.M, c.ld, c.n, g.plan_dev);
     } else {
         set_recompute_source(c, X_dev, dt, d, ld_x, nullptr, sigma2);
         RCD_TRY(launch_row_norms(X_dev, dt, n, d, ld_x, nullptr, c.sq, stream));
@@ -812,8 +878,9 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
         // stored if the largest class, alone, fits; else recompute everything
         const size_t need_one = group_base + group_fixed_bytes(1, K) + class_state_bytes(max_count, K, true) +
                                 up256((size_t)max_count * 4);
-        stored = need_one <= workspace_bytes;
+        stored = need_one <= workspace_bytes && stored_supported(max_count, K);
     }
+    if (stored && !stored_supported(max_count, K)) return RCD_ERR_UNSUPPORTED;
     int l0 = 0;
     while (l0 < L) {
         // how many consecutive classes fit?
@@ -870,7 +937,7 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
             // contiguous in the descriptor array.  A recomputed sweep keeps the matrix cores
             // busy for milliseconds per round, so there is nothing for a second lane to hide.
             int nl = 1;
-            if (stored && !g_profile_on) nl = std::min(live, env_int("RCD_LANES", 3, 1, RCD_MAX_LANES));
+            if (stored && !g_profile_on) nl = std::min(live, env_int("RCD_LANES", 2, 1, RCD_MAX_LANES));
             std::vector<Group> lanes(nl);
             {
                 std::vector<double> cum(live + 1, 0.0);
@@ -886,6 +953,7 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
                     Group &sub = lanes[i];
                     sub.classes_dev = g.classes_dev + a;
                     sub.plan_dev = sub.plan_area[0] = g.plan_area[i];
+                    sub.wgmap_dev = sub.wg_area[0] = g.wg_area[i];
                     sub.obj_dev = g.obj_dev + (size_t)a * K;
                     sub.K = K;
                     sub.host.assign(g.host.begin() + a, g.host.begin() + b);

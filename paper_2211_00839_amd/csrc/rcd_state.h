@@ -8,22 +8,22 @@
 #include <stdint.h>
 
 #define RCD_KMAX 16          // must equal RCD_MAX_K of the public header
-#define RCD_TILE 256         // candidate columns per sweep tile, stored S (64 lanes x 4)
+#define RCD_TILE 256         // pitch granule of a stored matrix row (one wave reads 64 lanes x 4 floats at a time)
 #define RCD_TILE_RC 128      // candidate columns per sweep tile when S is recomputed
 #define RCD_ROWS_RC 256      // rows of one recomputed tile
 #define RCD_CMAX 32          // most row chunks a class's sweep is split into
-#define RCD_SWEEP_WAVES 8     // waves of a sweep workgroup: each takes an eighth of the chunk's rows
+#define RCD_SWEEP_WAVES 16    // waves of a stored-S sweep workgroup: each streams one candidate row at a time
 #define RCD_SWEEP_THREADS (64 * RCD_SWEEP_WAVES)
-#define RCD_ROW_ALIGN (4 * RCD_SWEEP_WAVES)   // rows per chunk are a multiple of this (4-row unroll per wave)
+#define RCD_SWEEP_LDS_FLOATS 32768   // LDS of a stored-S sweep workgroup: coverage of the evaluated blocks, one chunk of j
 #define RCD_STEP_THREADS 1024
 
 struct RcdClass {
     // ---- fixed for the run
-    float *M;            // n x ld working similarity; column p holds S(., perm[p])
+    float *M;            // stored S: n x ld, M[v][j] = S(j, v), read-only
     float *cur;          // K x ld coverage vectors cur_k(j) = max_{a in A_k} S(j,a)
-    float *part;         // RCD_CMAX x K x ld partial gain sums per row chunk
+    float *part;         // RCD_CMAX x K x ld partial gain sums per chunk (stored S: chunk of j; recompute: of rows)
     float *gain;         // K x ld finished gains, indexed by column position
-    int32_t *perm;       // ld: original (class-local) index held by column p
+    int32_t *perm;       // ld: class-local index of the candidate at list position (column) p
     int32_t *tilecnt;    // ld/RCD_TILE_RC arrival counters of the sweep's row chunks, per tile
     float *sq;           // recompute mode: squared norms of the class's rows
     int32_t *assign_out; // caller's arrays (global indexing through out_index)
@@ -43,9 +43,10 @@ struct RcdClass {
     int32_t t;           // steps taken
     int32_t done;
     int32_t nneed;       // blocks whose gains the next sweep must produce
-    int32_t C, rpc;      // row chunks of the next sweep, rows per chunk
+    int32_t C, rpc;      // chunks of the next sweep and their length (recompute: rows; stored S: j's per pass)
     int32_t tiles_done;  // arrival counter of the sweep's finished tiles
     int32_t need[RCD_KMAX];
+    int32_t cblk[RCD_KMAX];  // stored S: chunk partials that make up block k's current gain row
     int32_t cnt[RCD_KMAX];
     int32_t cap[RCD_KMAX];
     int32_t valid[RCD_KMAX];
@@ -71,4 +72,9 @@ struct RcdPlan {
     int32_t ndone;       // classes finished
     int32_t bad;         // set by validation kernels (buffer 0 only)
     int32_t pad[2];
+};
+
+// Stored-S sweep: which class a workgroup serves, and as which of how many.
+struct RcdWg {
+    int32_t cls, w, W, pad;
 };
