@@ -204,6 +204,35 @@ int sweep_setup()
     return RCD_OK;
 }
 
+// Fast path of the matrix-core kernels: feature rows that can go straight from global memory
+// into LDS a whole 128-byte line at a time.
+bool rows_fit_fast_path(const void *X, int dt, int64_t d, int64_t ldx)
+{
+    const int64_t esz = dt == RCD_F32 ? 4 : 2;
+    return (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ((ldx * esz) % 16) == 0 && d * esz >= sim::pipe::LINE &&
+           (d * esz) % sim::pipe::LINE == 0;
+}
+
+// The fast kernels use more LDS than a kernel may by default: raise their limit once.
+bool g_fast_ready = false;
+int fast_setup()
+{
+    if (!g_fast_ready) {
+        const void *sim_kernels[] = {reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float>),
+                                     reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16>)};
+        for (const void *k : sim_kernels)
+            HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, sim::pipe::LDS_BYTES));
+        const void *rc_kernels[] = {reinterpret_cast<const void *>(&rcd_k_round_rc_fast<float, true>),
+                                    reinterpret_cast<const void *>(&rcd_k_round_rc_fast<float, false>),
+                                    reinterpret_cast<const void *>(&rcd_k_round_rc_fast<__bf16, true>),
+                                    reinterpret_cast<const void *>(&rcd_k_round_rc_fast<__bf16, false>)};
+        for (const void *k : rc_kernels)
+            HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, RCD_RC_FAST_LDS));
+        g_fast_ready = true;
+    }
+    return RCD_OK;
+}
+
 int ensure_pinned()
 {
     if (!g_pinned) {
@@ -234,6 +263,7 @@ struct Lane {
     int ncls = 0, rounds = 16, items_ub = 0, round_no = 0;
     bool recompute = false, fused = false, prof = false, finished = false;
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
+    size_t round_rc_lds = 0;   // dynamic LDS of the recompute sweep (fast path only)
     void (*apply_rc)(RcdClass *, int) = nullptr;
     int sweep_wgs = 0;       // stored S: workgroups of the sweep launch
     dim3 apply_rc_grid;
@@ -314,22 +344,23 @@ struct Lane {
                                g->plan_dev);
 
         for (int i = 0; i < RCD_SLOTS; ++i) HIP_TRY(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
-        const int esz = first.dt == RCD_F32 ? 4 : 2;
-        const bool fast = recompute && (reinterpret_cast<uintptr_t>(first.X) & 15) == 0 &&
-                          ((first.ldx64 * esz) % 16) == 0 && ((int64_t)first.d * esz) % sim::ROWB == 0;
         // One launch per round (sweep + step loops fused) pays off when few classes are in
         // flight; with many, the sweep is bandwidth-bound and the step loops get their own launch.
         fused = recompute && env_int("RCD_FUSED", ncls <= 2 ? 1 : 0, 0, 1) != 0;
         if (recompute) {
-            if (first.dt == RCD_F32) {
-                round_rc = fused ? (fast ? rcd_k_round_rc<float, true, true> : rcd_k_round_rc<float, false, true>)
-                                 : (fast ? rcd_k_round_rc<float, true, false> : rcd_k_round_rc<float, false, false>);
-                apply_rc = rcd_k_apply_rc<float>;
+            const bool fast = first.tw == RCD_TILE_FAST;
+            const bool f32 = first.dt == RCD_F32;
+            if (fast) {
+                RCD_TRY(fast_setup());
+                round_rc_lds = RCD_RC_FAST_LDS;
+                round_rc = f32 ? (fused ? rcd_k_round_rc_fast<float, true> : rcd_k_round_rc_fast<float, false>)
+                               : (fused ? rcd_k_round_rc_fast<__bf16, true> : rcd_k_round_rc_fast<__bf16, false>);
             } else {
-                round_rc = fused ? (fast ? rcd_k_round_rc<__bf16, true, true> : rcd_k_round_rc<__bf16, false, true>)
-                                 : (fast ? rcd_k_round_rc<__bf16, true, false> : rcd_k_round_rc<__bf16, false, false>);
-                apply_rc = rcd_k_apply_rc<__bf16>;
+                round_rc_lds = 0;
+                round_rc = f32 ? (fused ? rcd_k_round_rc<float, true> : rcd_k_round_rc<float, false>)
+                               : (fused ? rcd_k_round_rc<__bf16, true> : rcd_k_round_rc<__bf16, false>);
             }
+            apply_rc = f32 ? rcd_k_apply_rc<float> : rcd_k_apply_rc<__bf16>;
         }
         launches = 3;
         round_no = 0;
@@ -362,7 +393,8 @@ struct Lane {
         for (int r = 0; r < rounds; ++r) {
             const int buf = fused ? (round_no & 1) : 0;
             if (recompute)
-                hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), 0, stream, g->classes_dev, g->plan_dev, buf);
+                hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), round_rc_lds, stream, g->classes_dev, g->plan_dev,
+                                   buf);
             else
                 hipLaunchKernelGGL(rcd_k_sweep_rows, dim3(sweep_wgs), dim3(RCD_SWEEP_THREADS),
                                    RCD_SWEEP_LDS_FLOATS * 4, stream, (const RcdClass *)g->classes_dev,
@@ -547,22 +579,36 @@ int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, 
                       float sigma2, float *S, int64_t ld_s, int ncols_pad, float *sq, hipStream_t stream)
 {
     const float exp_scale = (float)(-1.4426950408889634 / (2.0 * (double)sigma2));
-    const dim3 grid((unsigned)((ncols_pad + sim::BN - 1) / sim::BN), (unsigned)((n + sim::BM - 1) / sim::BM));
     const unsigned nblk = (unsigned)((n + 3) / 4);
-    const int esz = dt == RCD_F32 ? 4 : 2;
-    const bool fast = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ((ldx * esz) % 16) == 0 && (d * esz) % sim::ROWB == 0;
-    if (dt == RCD_F32) {
+    const bool fast = rows_fit_fast_path(X, dt, d, ldx);
+    if (dt == RCD_F32)
         hipLaunchKernelGGL(sim::k_row_norms<float>, dim3(nblk), dim3(256), 0, stream, (const float *)X,
                            (long long)ldx, row_index, (int)n, (int)d, sq);
-        auto kern = fast ? sim::k_gram_rbf<float, true> : sim::k_gram_rbf<float, false>;
-        hipLaunchKernelGGL(kern, grid, dim3(sim::THREADS), 0, stream, (const float *)X, (long long)ldx, row_index,
-                           (int)n, (int)d, (const float *)sq, exp_scale, S, (long long)ld_s, ncols_pad);
-    } else {
+    else
         hipLaunchKernelGGL(sim::k_row_norms<__bf16>, dim3(nblk), dim3(256), 0, stream, (const __bf16 *)X,
                            (long long)ldx, row_index, (int)n, (int)d, sq);
-        auto kern = fast ? sim::k_gram_rbf<__bf16, true> : sim::k_gram_rbf<__bf16, false>;
-        hipLaunchKernelGGL(kern, grid, dim3(sim::THREADS), 0, stream, (const __bf16 *)X, (long long)ldx, row_index,
-                           (int)n, (int)d, (const float *)sq, exp_scale, S, (long long)ld_s, ncols_pad);
+    if (fast) {
+        RCD_TRY(fast_setup());
+        const int64_t tiles = ((n + sim::pipe::TM - 1) / sim::pipe::TM) * ((ncols_pad + sim::pipe::TN - 1) / sim::pipe::TN);
+        const dim3 grid((unsigned)((tiles + 7) / 8 * 8));
+        if (dt == RCD_F32)
+            hipLaunchKernelGGL(sim::k_gram_rbf_fast<float>, grid, dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream,
+                               (const float *)X, (long long)ldx, row_index, (int)n, (int)d, (const float *)sq,
+                               exp_scale, S, (long long)ld_s, ncols_pad);
+        else
+            hipLaunchKernelGGL(sim::k_gram_rbf_fast<__bf16>, grid, dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream,
+                               (const __bf16 *)X, (long long)ldx, row_index, (int)n, (int)d, (const float *)sq,
+                               exp_scale, S, (long long)ld_s, ncols_pad);
+    } else {
+        const dim3 grid((unsigned)((ncols_pad + sim::BN - 1) / sim::BN), (unsigned)((n + sim::BM - 1) / sim::BM));
+        if (dt == RCD_F32)
+            hipLaunchKernelGGL(sim::k_gram_rbf<float>, grid, dim3(sim::THREADS), 0, stream, (const float *)X,
+                               (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
+                               (long long)ld_s, ncols_pad);
+        else
+            hipLaunchKernelGGL(sim::k_gram_rbf<__bf16>, grid, dim3(sim::THREADS), 0, stream, (const __bf16 *)X,
+                               (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
+                               (long long)ld_s, ncols_pad);
     }
     HIP_TRY(hipGetLastError());
     return RCD_OK;
@@ -592,6 +638,7 @@ void set_recompute_source(RcdClass &c, const void *X, int dt, int64_t d, int64_t
     c.ldx = (int)std::min<int64_t>(ldx, 0x7fffffff);
     c.dt = dt;
     c.exp_scale = (float)(-1.4426950408889634 / (2.0 * (double)sigma2));
+    c.tw = rows_fit_fast_path(X, dt, d, ldx) ? RCD_TILE_FAST : RCD_TILE_RC;
 }
 
 int check_workspace(const void *ws, size_t have, size_t need)

@@ -9,7 +9,8 @@
 
 #define RCD_KMAX 16          // must equal RCD_MAX_K of the public header
 #define RCD_TILE 256         // pitch granule of a stored matrix row (one wave reads 64 lanes x 4 floats at a time)
-#define RCD_TILE_RC 128      // candidate columns per sweep tile when S is recomputed
+#define RCD_TILE_RC 128      // candidate columns per sweep tile when S is recomputed, general path
+#define RCD_TILE_FAST 256    // the same on the fast path (aligned feature rows, a multiple of 128 bytes long)
 #define RCD_ROWS_RC 256      // rows of one recomputed tile
 #define RCD_CMAX 32          // most row chunks a class's sweep is split into
 #define RCD_SWEEP_WAVES 16    // waves of a stored-S sweep workgroup: each streams one candidate row at a time
@@ -34,7 +35,7 @@ struct RcdClass {
     int64_t ldx64;
     int32_t n, ld, K, total;    // total = sum of quotas
     int32_t d, ldx, dt, mode;
-    int32_t tw;          // sweep tile width in columns
+    int32_t tw;          // sweep tile width in columns (recompute mode: RCD_TILE_FAST selects the fast path)
     int32_t row_align;   // rows per chunk are a multiple of this
     float exp_scale;     // -log2(e) / (2 sigma^2)
     int32_t target_items;       // sweep workgroups this class should be split into

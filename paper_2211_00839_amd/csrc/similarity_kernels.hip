@@ -5,6 +5,7 @@
 // order, so the result is symmetric bit for bit; the diagonal is forced to 1.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace sim {
 
@@ -30,27 +31,25 @@ template <> struct Elem<__bf16> { static constexpr int BK = 32; };
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // The similarity from the Gram value g = x_i . x_j and the pre-scaled norms
-// sq_s = |x|^2 * c, c = -log2(e) / (2 sigma^2):  2^min(0, sq_i_s + sq_j_s - 2 c g).
+// sq_s = |x|^2 * c, c = -log2(e) / (2 sigma^2):  min(1, 2^(sq_i_s + sq_j_s - 2 c g)),
+// the min being the clamp-to-[0,1] output modifier of the exponential instruction.
 // Every kernel that needs a similarity goes through this one expression, so that
 // S(i,j) is the same bits wherever it is computed.
 __device__ __forceinline__ float rbf_value(float gram, float sqi_s, float sqj_s, float scale2)
 {
-    return fast_exp2(fminf(fmaf(gram, scale2, sqi_s + sqj_s), 0.f));
+    return __builtin_amdgcn_fmed3f(fast_exp2(fmaf(gram, scale2, sqi_s + sqj_s)), 0.f, 1.f);
 }
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
 
 // One 16-byte chunk of row `row`, k range [k, k + 16/sizeof(T)), zero beyond d.
-// FAST: rows are 16-byte aligned and d is a multiple of the stage depth, so every
-// chunk is one aligned vector load and the main loop carries no branches.
-template <typename T, bool FAST>
+template <typename T>
 __device__ __forceinline__ uint4 load_chunk(const T *__restrict__ X, long long ldx, int row, int k, int d,
                                             bool vec_ok)
 {
     constexpr int E = CHUNK / (int)sizeof(T);
     const T *p = X + (size_t)row * ldx + k;
-    if constexpr (FAST) return *reinterpret_cast<const uint4 *>(p);
     if (vec_ok && k + E <= d) return *reinterpret_cast<const uint4 *>(p);
     union { uint4 u; T e[E]; } tmp;
     tmp.u = make_uint4(0, 0, 0, 0);
@@ -82,7 +81,7 @@ k_row_norms(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ 
 }
 
 // ---------------------------------------------------------------------------
-// Gram main loop of one 256 x 128 tile: acc += X[arow] . X[brow]^T over all of d.
+// General path.  Gram main loop of one 256 x 128 tile: acc += X[arow] . X[brow]^T over all of d.
 // 4 waves as 2 x 2; a wave owns 128 x 64 = 4 x 2 MFMA 32x32 tiles (a 4x2 wave
 // tile needs 0.75 KB of LDS reads per MFMA, which the LDS can feed at the full
 // MFMA rate; a 2x2 one cannot).  k advances 64 bytes per row and stage (32 bf16
@@ -131,14 +130,14 @@ __device__ __forceinline__ void gram_stage_mma(const unsigned char *__restrict__
 // register sets hold the stages in flight, the oldest is written to the free LDS
 // buffer right after the multiply of the current stage, then its registers are
 // reloaded with the stage NPRE ahead.
-template <typename T, bool FAST>
+template <typename T>
 __device__ __forceinline__ void gram_mainloop(const T *__restrict__ X, long long ldx, int d, bool vec_ok,
                                               const int (&arow)[4], const int (&brow)[2],
                                               unsigned char *__restrict__ lds, f32x16 (&acc)[4][2])
 {
     constexpr int BK = Elem<T>::BK;
     constexpr int EPC = CHUNK / (int)sizeof(T);   // elements per chunk
-    constexpr int NPRE = 1;   // generic path only: unaligned rows or ragged d; the aligned case uses gram_mainloop_dma
+    constexpr int NPRE = 1;   // general path only: unaligned rows or ragged d; the aligned case uses pipe::Pipe
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1;
@@ -157,9 +156,9 @@ __device__ __forceinline__ void gram_mainloop(const T *__restrict__ X, long long
     auto load_stage = [&](int set, int stage) {
         const int k = stage * BK + cpart * EPC;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) ra[set][u] = load_chunk<T, FAST>(X, ldx, arow[u], k, d, vec_ok);
+        for (int u = 0; u < 4; ++u) ra[set][u] = load_chunk<T>(X, ldx, arow[u], k, d, vec_ok);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) rb[set][u] = load_chunk<T, FAST>(X, ldx, brow[u], k, d, vec_ok);
+        for (int u = 0; u < 2; ++u) rb[set][u] = load_chunk<T>(X, ldx, brow[u], k, d, vec_ok);
     };
     auto store_stage = [&](int set, unsigned char *dst) {
 #pragma unroll
@@ -215,26 +214,40 @@ __device__ __forceinline__ void gram_mainloop(const T *__restrict__ X, long long
 }
 
 // ---------------------------------------------------------------------------
-// Fast main loop (rows 16-byte aligned, d a multiple of the stage depth): the
-// stages go from global memory straight into LDS (global_load_lds_dwordx4: lane
-// L of a wave drops its 16 bytes at LDS base + 16 L), three stages deep, no
-// registers and no ds_write in between.  Rows are 64 bytes in LDS, unpadded;
-// the 16-byte chunk c of row r sits at chunk position c ^ swizzle(r), which
-// keeps both 8- and 16-lane groups of a ds_read_b128 on distinct banks.  The
-// loads are issued from inline asm so that their completion is awaited by
-// explicit vmcnt counts (stage s must have landed, younger stages may fly); the
+// Fast path (rows 16-byte aligned, row length a multiple of 128 bytes): a 256 x 256
+// tile per 256-thread workgroup, 4 waves as 2 x 2, each wave 4 x 4 MFMA 32x32
+// tiles (the 256 accumulator registers of a lane fill the AGPR file, one wave per
+// SIMD).  Per unit of k the tile reads 512 feature rows for 65 536 multiply-adds,
+// the least traffic between L2 and the compute unit a single workgroup can have.
+//
+// The features go from global memory straight into LDS (global_load_lds_dwordx4:
+// lane L of a wave drops its 16 bytes at LDS base + 16 L), one whole 128-byte
+// cache line per row and stage, two 64 KB stages.  The 16-byte chunk c of row r
+// sits at chunk position c ^ ((r >> 1) & 7), which spreads the 16 rows that one
+// pass of a ds_read_b128 touches over all 64 banks.  The loads are issued from
+// inline asm so that their completion is awaited by explicit vmcnt counts; the
 // compiler would otherwise wait for all of them at every barrier.
+//
+// One stage is four k sub-steps of 16 multiplies (bf16; 64 for fp32).  All LDS
+// reads of a stage are issued, one after each multiply, by the end of sub-step 1,
+// so the barrier that frees the stage's buffer sits early in sub-step 2, and the
+// 16 loads of stage s+2 go out one every other multiply over the rest of the stage:
+// a wave issues in order, and a burst of loads backs up the memory pipeline and
+// holds up the multiplies queued behind it.  sched_barrier keeps the compiler from
+// re-clustering what is interleaved here by hand.
 // ---------------------------------------------------------------------------
-constexpr int DMA_STAGES = 3;
-constexpr int DMA_STAGE_BYTES = (BM + BN) * ROWB;      // 24 KB
-constexpr int DMA_LDS_BYTES = DMA_STAGES * DMA_STAGE_BYTES;
+namespace pipe {
 
-__device__ __forceinline__ int lds_swizzle(int row)
-{
-    return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
-}
+constexpr int TM = 256, TN = 256;        // tile rows (x_i) and columns (x_j)
+constexpr int LINE = 128;                // bytes of k per row and stage
+constexpr int STAGE = (TM + TN) * LINE;  // 64 KB
+constexpr int NSTAGE = 2;
+constexpr int LDS_BYTES = NSTAGE * STAGE;
+constexpr int NLOAD = STAGE / (THREADS * CHUNK);   // 16 loads per lane and stage
 
-__device__ __forceinline__ void dma16(const void *gptr, unsigned lds_addr)
+__device__ __forceinline__ int swizzle(int row) { return (row >> 1) & 7; }
+
+__device__ __forceinline__ void load_to_lds(const void *gptr, unsigned lds_addr)
 {
     unsigned saved;
     asm volatile("s_mov_b32 %0, m0\n\t"
@@ -246,114 +259,305 @@ __device__ __forceinline__ void dma16(const void *gptr, unsigned lds_addr)
                  : "v"(gptr), "s"(lds_addr)
                  : "memory");
 }
-
-// Tile row (0..255 = A rows, 256..383 = B rows) and k chunk that lane `lane` of
-// wave `wave` fetches with its u-th load of a stage.
-__device__ __forceinline__ void dma_slot(int wave, int u, int lane, int *tile_row, int *chunk)
+// 4 bytes per lane: lane L's word lands at LDS address lds_addr + 4 L
+__device__ __forceinline__ void load_dword_to_lds(const void *gptr, unsigned lds_addr)
 {
-    const int row = (wave * 6 + u) * 16 + (lane >> 2);
+    unsigned saved;
+    asm volatile("s_mov_b32 %0, m0\n\t"
+                 "s_mov_b32 m0, %2\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dword %1, off\n\t"
+                 "s_mov_b32 m0, %0"
+                 : "=&s"(saved)
+                 : "v"(gptr), "s"(lds_addr)
+                 : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void pin_schedule() { __builtin_amdgcn_sched_barrier(0); }
+
+// Tile row (0..255 = x_i rows, 256..511 = x_j rows) and 16-byte chunk of the row's
+// line that lane `lane` of wave `wave` fetches with its u-th load of a stage.
+// Waves 0 and 1 fetch the x_i rows, waves 2 and 3 the x_j rows.
+__device__ __forceinline__ void load_slot(int wave, int u, int lane, int *tile_row, int *chunk)
+{
+    const int row = (wave * NLOAD + u) * 8 + (lane >> 3);
     *tile_row = row;
-    *chunk = (lane & 3) ^ lds_swizzle(row);
+    *chunk = (lane & 7) ^ swizzle(row);
 }
 
-// gp[u]: address of this lane's chunk of stage 0 for its u-th load (see dma_slot).
-template <typename T>
-__device__ __forceinline__ void gram_mainloop_dma(const T *const (&gp)[6], int d, unsigned char *lds,
-                                                  f32x16 (&acc)[4][2])
-{
-    constexpr int BK = Elem<T>::BK;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 1, wc = wave & 1;
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+struct Frags { uint4 v[8]; };   // v[0..3]: x_i fragments (32 rows each), v[4..7]: x_j fragments
 
-    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds;
-    auto issue = [&](int stage, int buf) {
+// The multiplies of one k sub-step; hook(i) runs right after the i-th of the first 16.
+template <typename T, typename Hook>
+__device__ __forceinline__ void multiply(const Frags &f, f32x16 (&acc)[4][4], Hook hook)
+{
+    if constexpr (sizeof(T) == 2) {
 #pragma unroll
-        for (int u = 0; u < 6; ++u)
-            dma16(gp[u] + (size_t)stage * BK, lds_base + buf * DMA_STAGE_BYTES + (wave * 6 + u) * 1024);
-    };
-    // fragment addresses inside a stage: lanes 0-31 take k chunk 2 kk, lanes 32-63 chunk 2 kk + 1
-    const int hi = lane >> 5;
-    int aoff[4][2], boff[2][2];
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
+            for (int b = 0; b < 4; ++b) {
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, f.v[a]), __builtin_bit_cast(bf16x8, f.v[4 + b]), acc[a][b], 0, 0, 0);
+                pin_schedule();
+                hook(a * 4 + b);
+                pin_schedule();
+            }
+    } else {
+        // four 32x32x2 products per fragment pair; lanes<32 carry k = e, lanes>=32 carry k = 4+e,
+        // for both operands alike, so every k of the group is used exactly once
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const int row = wr * 128 + 32 * m + (lane & 31);
-            aoff[m][kk] = row * ROWB + (((kk * 2 + hi) ^ lds_swizzle(row)) << 4);
-        }
+        for (int e = 0; e < 4; ++e)
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const int row = BM + wc * 64 + 32 * m + (lane & 31);
-            boff[m][kk] = row * ROWB + (((kk * 2 + hi) ^ lds_swizzle(row)) << 4);
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const f32x4 va = __builtin_bit_cast(f32x4, f.v[a]);
+                    const f32x4 vb = __builtin_bit_cast(f32x4, f.v[4 + b]);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], vb[e], acc[a][b], 0, 0, 0);
+                    if (e == 0) {
+                        pin_schedule();
+                        hook(a * 4 + b);
+                        pin_schedule();
+                    }
+                }
+    }
+}
+
+template <typename T>
+struct Pipe {
+    unsigned char *lds;
+    unsigned wave_dst;            // LDS address of this wave's first load of a stage
+    int aoff, boff, sw16, hi16;   // this lane's fragment rows, its swizzle and k half, in bytes
+    const unsigned char *gp[NLOAD];   // this lane's chunk of the next stage to load, per load slot
+
+    __device__ __forceinline__ void init(unsigned char *lds_)
+    {
+        lds = lds_;
+        const int tid = threadIdx.x, lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int wr = wave >> 1, wc = wave & 1;
+        const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds;
+        wave_dst = lds_base + wave * (NLOAD * 1024);
+        aoff = (wr * 128 + (lane & 31)) * LINE;
+        boff = (TM + wc * 128 + (lane & 31)) * LINE;
+        sw16 = swizzle(lane & 31) << 4;     // fragment rows differ from lane & 31 by multiples of 32
+        hi16 = (lane >> 5) << 4;            // lanes 0-31 take the first 16 bytes of a 32-byte k group
+    }
+    __device__ __forceinline__ void load1(int buf, int u)
+    {
+        load_to_lds(gp[u], wave_dst + buf * STAGE + u * 1024);
+        gp[u] += LINE;
+    }
+    // fragment i (0..3 x_i, 4..7 x_j) of k sub-step kk of the stage in buffer buf
+    __device__ __forceinline__ void read1(Frags &f, int buf, int kk, int i)
+    {
+        const unsigned char *base = lds + buf * STAGE;
+        const int pos = (kk * 32 + hi16) ^ sw16;
+        if (i < 4) f.v[i] = *reinterpret_cast<const uint4 *>(base + aoff + pos + i * 32 * LINE);
+        else f.v[i] = *reinterpret_cast<const uint4 *>(base + boff + pos + (i - 4) * 32 * LINE);
+    }
+    // Start the loads of a tile's first two stages (gp set, nstage >= 1).
+    __device__ __forceinline__ void start(int nstage)
+    {
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) load1(0, u);
+        if (nstage > 1) {
+#pragma unroll
+            for (int u = 0; u < NLOAD; ++u) load1(1, u);
         }
     }
-    auto mma = [&](const unsigned char *cur) {
+    // The whole k loop of a tile whose start() has been called; acc = sum over all of k.
+    // Ends with a barrier: the ring is free in every wave.
+    __device__ __forceinline__ void run(int nstage, f32x16 (&acc)[4][4])
+    {
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            uint4 fa[4], fb[2];
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int m = 0; m < 4; ++m) fa[m] = *reinterpret_cast<const uint4 *>(cur + aoff[m][kk]);
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int m = 0; m < 2; ++m) fb[m] = *reinterpret_cast<const uint4 *>(cur + boff[m][kk]);
-            if constexpr (sizeof(T) == 2) {
+                for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+        if (nstage > 1) wait_loads<NLOAD>();
+        else wait_loads<0>();
+        __builtin_amdgcn_s_barrier();
+        Frags f0, f1, f2, f3;     // k sub-steps 0..3 of the current stage
 #pragma unroll
-                for (int a = 0; a < 4; ++a)
-#pragma unroll
-                    for (int b = 0; b < 2; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, fa[a]), __builtin_bit_cast(bf16x8, fb[b]), acc[a][b], 0, 0, 0);
+        for (int i = 0; i < 8; ++i) read1(f0, 0, 0, i);
+        auto nothing = [](int) {};
+        int buf = 0;
+        // MORE: another stage follows.  REFILL: stage s+2 exists and takes this stage's buffer.
+        auto stage = [&](auto more_tag, auto refill_tag) {
+            constexpr bool MORE = decltype(more_tag)::value, REFILL = decltype(refill_tag)::value;
+            multiply<T>(f0, acc, [&](int i) { if (i < 8) read1(f1, buf, 1, i); });
+            multiply<T>(f1, acc, [&](int i) {
+                if (i < 8) read1(f2, buf, 2, i);
+                else read1(f3, buf, 3, i - 8);
+            });
+            if constexpr (MORE) {
+                multiply<T>(f2, acc, [&](int i) {
+                    if (i == 3) {
+                        // my loads of stage s+1 have landed and my reads of stage s are complete;
+                        // after the barrier that holds for every wave
+                        wait_loads<0>();
+                        wait_lds();
+                        __builtin_amdgcn_s_barrier();
+                    }
+                    if constexpr (REFILL)
+                        if (i >= 4 && (i & 1) == 0) load1(buf, (i - 4) >> 1);     // loads 0..5
+                });
+                multiply<T>(f3, acc, [&](int i) {
+                    if (i < 8) read1(f0, buf ^ 1, 0, i);
+                    if constexpr (REFILL)
+                        if (i < 10) load1(buf, 6 + i);                            // loads 6..15
+                });
             } else {
+                multiply<T>(f2, acc, nothing);
+                multiply<T>(f3, acc, nothing);
+            }
+            buf ^= 1;
+        };
+        int s = 0;
+        for (; s + 2 < nstage; ++s) stage(std::true_type{}, std::true_type{});
+        if (s + 1 < nstage) stage(std::true_type{}, std::false_type{});
+        stage(std::false_type{}, std::false_type{});
+        wait_lds();
+        __builtin_amdgcn_s_barrier();
+    }
+};
+
+// One accumulator element, fetched from the accumulator register file at the point of use.
+// The explicit read keeps the register allocator from moving a whole tile's 256 accumulators
+// into ordinary registers at once, which leaves room for nothing else.
+__device__ __forceinline__ float acc_read(float a)
+{
+    float v;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
+// The workgroups of a launch are dealt round-robin to the 8 XCDs, each with an L2 of its own.
+// Tile number t of workgroup w: every XCD owns a contiguous run of the tile list, and the
+// list walks the tile grid in bands of 8 tile rows, down the band first, so that the 32
+// workgroups an XCD runs side by side share their feature rows in its L2.
+__device__ __forceinline__ bool tile_of_workgroup(int w, int nwg, int tiles_m, int tiles_n, int *ti, int *tj)
+{
+    const int per = (nwg + 7) >> 3;
+    const int t = (w & 7) * per + (w >> 3);
+    if (t >= tiles_m * tiles_n) return false;
+    constexpr int BAND = 8;
+    const int band = t / (BAND * tiles_n);
+    const int rows_in_band = min(BAND, tiles_m - band * BAND);
+    const int r = t - band * BAND * tiles_n;
+    *ti = band * BAND + r % rows_in_band;
+    *tj = r / rows_in_band;
+    return true;
+}
+
+} // namespace pipe
+
+// Gram tile + Gaussian epilogue, fast path.  grid = tiles rounded up to a multiple of 8,
+// dynamic LDS = pipe::LDS_BYTES.  Columns n .. ncols_pad-1 of the output are written as 0.
+template <typename T>
+__global__ void __launch_bounds__(THREADS, 1)
+k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
+                const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
+                int ncols_pad)
+{
+    using namespace pipe;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const int tiles_m = (n + TM - 1) / TM, tiles_n = (ncols_pad + TN - 1) / TN;
+    int ti, tj;
+    if (!tile_of_workgroup((int)blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, &ti, &tj)) return;
+    const int i0 = ti * TM, j0 = tj * TN;
+
+    if (j0 >= n) {
+        // tile entirely in the zero padding of the output pitch
+        for (int e = tid; e < TM * TN; e += THREADS) {
+            const int i = i0 + e / TN, j = j0 + e % TN;
+            if (i < n && j < ncols_pad) S[(size_t)i * lds_out + j] = 0.f;
+        }
+        return;
+    }
+
+    Pipe<T> p;
+    p.init(lds);
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+    for (int u = 0; u < NLOAD; ++u) {
+        int trow, chunk;
+        load_slot(wave, u, lane, &trow, &chunk);
+        const int gi = trow < TM ? min(i0 + trow, n - 1) : min(j0 + trow - TM, n - 1);
+        const int row = row_index ? row_index[gi] : gi;
+        p.gp[u] = reinterpret_cast<const unsigned char *>(X + (size_t)row * ldx) + chunk * CHUNK;
+    }
+    const int nstage = (int)(((long long)d * (int)sizeof(T)) / LINE);
+    p.start(nstage);
+    // what the epilogue needs from memory is fetched under the k loop
+    const float my_sq_row = (i0 + tid < n) ? sq[i0 + tid] * exp_scale : 0.f;
+    float sqj[4];
+    int jj[4];
 #pragma unroll
-                    for (int a = 0; a < 4; ++a)
+    for (int b = 0; b < 4; ++b) {
+        jj[b] = j0 + wc * 128 + b * 32 + (lane & 31);
+        sqj[b] = jj[b] < n ? sq[jj[b]] * exp_scale : 0.f;
+    }
+    f32x16 acc[4][4];
+    p.run(nstage, acc);
+
+    // epilogue: a lane holds column (lane & 31) of each 32-wide block b, rows
+    // 32 a + 8 rq + 4 (lane >> 5) + e.  The row norms go through LDS (the ring is idle).
+    float *sq_rows = reinterpret_cast<float *>(lds);
+    sq_rows[tid] = my_sq_row;
+    __syncthreads();
+    const float scale2 = -2.f * exp_scale;
+    const int r0 = i0 + wr * 128 + (lane >> 5) * 4;
+    float *dst0 = S + (size_t)r0 * lds_out + (j0 + wc * 128 + (lane & 31));
+    // one running row pointer per lane: rows advance +1 +1 +1 +5 through the accumulator layout
+    const long long step1 = lds_out, step5 = 5 * lds_out;
+    auto epilogue = [&](auto plain_tag) {
+        constexpr bool PLAIN = decltype(plain_tag)::value;   // interior tile off the diagonal: no checks
+        float *dst = dst0;
+        int i = r0;
 #pragma unroll
-                        for (int b = 0; b < 2; ++b) {
-                            const f32x4 va = __builtin_bit_cast(f32x4, fa[a]);
-                            const f32x4 vb = __builtin_bit_cast(f32x4, fb[b]);
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], vb[e], acc[a][b], 0, 0, 0);
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int rl = wr * 128 + a * 32 + rq * 8 + (lane >> 5) * 4;
+                const float4 sqi4 = *reinterpret_cast<const float4 *>(sq_rows + rl);
+                const float sqi[4] = {sqi4.x, sqi4.y, sqi4.z, sqi4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        float v = rbf_value(acc_read(acc[a][b][rq * 4 + e]), sqi[e], sqj[b], scale2);
+                        if constexpr (PLAIN) {
+                            dst[b * 32] = v;
+                        } else {
+                            if (i == jj[b]) v = 1.f;
+                            if (i < n && jj[b] < ncols_pad) dst[b * 32] = jj[b] < n ? v : 0.f;
                         }
+                    }
+                    dst += (e == 3) ? step5 : step1;
+                    i += (e == 3) ? 5 : 1;
+                }
+                pin_schedule();
             }
         }
     };
-
-    const int nstage = d / BK;
-    issue(0, 0);
-    if (nstage > 1) issue(1, 1);
-    int s = 0;
-    // Before the barrier of iteration s this wave's loads of stage s have landed (the 6
-    // loads of stage s+1 may still fly); after it everyone's have, and everyone is done
-    // reading the buffer that stage s+2 is about to overwrite.
-    for (; s + 2 < nstage; ++s) {
-        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        issue(s + 2, (s + 2) % DMA_STAGES);
-        mma(lds + (s % DMA_STAGES) * DMA_STAGE_BYTES);
-    }
-    for (; s < nstage; ++s) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        mma(lds + (s % DMA_STAGES) * DMA_STAGE_BYTES);
-    }
-    __builtin_amdgcn_s_barrier();   // everyone is done with the ring
+    if (i0 + TM <= n && j0 + TN <= n && ti != tj) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 }
 
-// Gram tile + Gaussian epilogue.  grid = (column tiles, row tiles).
-template <typename T, bool FAST>
+// Gram tile + Gaussian epilogue, general path (any alignment, any d).  grid = (column tiles, row tiles).
+template <typename T>
 __global__ void __launch_bounds__(THREADS, 2)
 k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
            const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
            int ncols_pad)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[FAST ? DMA_LDS_BYTES : 2 * STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -370,18 +574,7 @@ k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ r
     }
 
     f32x16 acc[4][2];
-    if constexpr (FAST) {
-        const T *gp[6];
-#pragma unroll
-        for (int u = 0; u < 6; ++u) {
-            int trow, chunk;
-            dma_slot(wave, u, lane, &trow, &chunk);
-            const int gi = trow < BM ? min(i0 + trow, n - 1) : min(j0 + trow - BM, n - 1);
-            const int row = row_index ? row_index[gi] : gi;
-            gp[u] = X + (size_t)row * ldx + chunk * (CHUNK / (int)sizeof(T));
-        }
-        gram_mainloop_dma<T>(gp, d, lds, acc);
-    } else {
+    {
         const bool vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0) && ((ldx * (long long)sizeof(T)) % 16 == 0);
         int arow[4], brow[2];
 #pragma unroll
@@ -394,7 +587,7 @@ k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ r
             const int bj = min(j0 + (tid >> 2) + 64 * u, n - 1);
             brow[u] = row_index ? row_index[bj] : bj;
         }
-        gram_mainloop<T, false>(X, ldx, d, vec_ok, arow, brow, lds, acc);
+        gram_mainloop<T>(X, ldx, d, vec_ok, arow, brow, lds, acc);
     }
 
     // epilogue: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane>>5) + (r&3).
