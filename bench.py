@@ -96,7 +96,7 @@ def extra_kernels(rcd, si, torch):
     ms = e0.elapsed_time(e1) / reps
     tf = 2.0 * n * n * d / (ms * 1e-3) / 1e12
     res["similarity_large_class"] = {
-        "kernel": "sim::k_gram_rbf<bf16> (+ row norms)", "shape": f"n={n} d={d} bf16 -> fp32 S", "ms": ms,
+        "kernel": "sim::k_gram_rbf_fast<bf16> (+ row norms)", "shape": f"n={n} d={d} bf16 -> fp32 S", "ms": ms,
         "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
                      "frac": tf / MFMA_PEAK_TFLOPS["bf16"],
                      "flops": "2 n^2 d, every tile computed (symmetry not exploited)"}}
@@ -111,7 +111,7 @@ def extra_kernels(rcd, si, torch):
     flops = 2.0 * st["entries_streamed"] * d
     tf = flops / (prof["sweep_ms"] * 1e-3) / 1e12 if prof["sweep_ms"] > 0 else 0.0
     res["recompute_sweep_large_class"] = {
-        "kernel": "rcd_k_round_rc<bf16> (S tiles rebuilt by MFMA inside the gain sweep)",
+        "kernel": "rcd_k_round_rc_fast<bf16> (S tiles rebuilt by MFMA inside the gain sweep)",
         "shape": f"n={n} d={d} bf16, K=8, first {st['steps']} greedy steps, {st['sweeps']} sweeps",
         "sweep_ms_total": prof["sweep_ms"], "steps_ms_total": prof["steps_ms"], "apply_ms_total": prof["apply_ms"],
         "useful_evals_per_s": st["useful_evals"] / ((prof["sweep_ms"] + prof["steps_ms"] + prof["apply_ms"]) * 1e-3),
