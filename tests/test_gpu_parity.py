@@ -62,6 +62,48 @@ def test_similarity_bf16(rcd, n, d):
     assert np.all(np.diag(S) == 1.0)
 
 
+@pytest.mark.parametrize("dtype,n,d", [("f32", 1, 32), ("f32", 255, 32), ("f32", 256, 96), ("f32", 257, 32),
+                                       ("bf16", 300, 64), ("bf16", 770, 192), ("f32", 1025, 64), ("bf16", 1300, 128)])
+def test_similarity_fast_path_edges(rcd, dtype, n, d):
+    """Rows that are a whole number of 128-byte lines take the direct-to-LDS 256 x 256 pipeline:
+    one, two and three stages of k, class sizes around the tile edge and across several tiles."""
+    print(f"similarity fast path {dtype} n={n} d={d}", flush=True)
+    X = si.make_class(seed=900 + n + d, n=n, d=d, dtype=dtype)
+    ref = oracle.similarity(X, float(d))
+    S = rcd.similarity(dev(X), float(d)).cpu().numpy()
+    assert rel_err(S, ref) <= 1e-5
+    assert np.array_equal(S, S.T)
+    assert np.all(np.diag(S) == 1.0)
+
+
+def test_similarity_fast_path_gather_pitched_input_and_output(rcd):
+    # aligned rows with a pitch (ld_x > d), a row gather and a pitched output: still the fast path
+    n, d = 420, 64
+    X = si.make_class(seed=17, n=n, d=d)
+    wide = np.zeros((n, d + 32), dtype=np.float32)
+    wide[:, :d] = X
+    wide[:, d:] = 1e30                                    # must never be read as features
+    idx = np.random.default_rng(1).permutation(n)[:333].astype(np.int32)
+    ref = oracle.similarity(X[idx], float(d))
+    out = torch.full((333, 400), -7.0, dtype=torch.float32, device="cuda")
+    rcd.similarity(dev(wide)[:, :d], float(d), row_index=dev(idx), out=out[:, :333])
+    got = out.cpu().numpy()
+    assert rel_err(got[:, :333], ref) <= 1e-5
+    assert np.all(got[:, 333:] == -7.0)                  # nothing written past n in a row
+
+
+def test_similarity_misaligned_rows_take_the_general_path(rcd):
+    # same shape as a fast-path case, but the rows start 4 bytes off a 16-byte boundary
+    n, d = 300, 64
+    X = si.make_class(seed=18, n=n, d=d)
+    wide = np.zeros((n, d + 1), dtype=np.float32)
+    wide[:, 1:] = X
+    ref = oracle.similarity(X, float(d))
+    S = rcd.similarity(dev(wide)[:, 1:], float(d)).cpu().numpy()
+    assert rel_err(S, ref) <= 1e-5
+    assert np.array_equal(S, S.T)
+
+
 def test_similarity_strided_rows_row_index_and_pitched_output(rcd):
     n, d = 150, 40
     X = si.make_class(seed=7, n=n, d=d)
@@ -224,6 +266,20 @@ def test_class_greedy_recompute_mode(rcd, dtype, n, d, r):
     same = np.mean(a2.cpu().numpy() == assign)
     print("  recompute vs stored agreement:", same, flush=True)
     assert np.allclose(f2, obj, rtol=1e-4)
+
+
+@pytest.mark.parametrize("dtype,n,d,r", [("f32", 600, 32, [1] * 16), ("bf16", 1000, 64, [3, 1, 2]),
+                                         ("f32", 257, 96, [1, 1]), ("bf16", 90, 128, [1, 2, 1, 2, 1])])
+def test_class_greedy_recompute_fast_path_edges(rcd, dtype, n, d, r):
+    """Recompute sweep on the 256 x 256 pipeline: one stage of k, sixteen blocks evaluated at once,
+    candidate tiles with a ragged tail, a class smaller than one tile."""
+    print(f"recompute fast path {dtype} n={n} d={d} K={len(r)}", flush=True)
+    X = si.make_class(seed=600 + n, n=n, d=d, G=8, dtype=dtype)
+    cap = oracle.quota(n, r)
+    assign, order, obj = rcd.partition_class(X=dev(X), cap=cap, sigma2=float(d))
+    S_gpu = rcd.similarity(dev(X), float(d)).cpu().numpy()
+    assert rel_err(S_gpu, oracle.similarity(X, float(d))) <= 1e-5
+    check_against_oracle(S_gpu, cap, assign.cpu().numpy(), order.cpu().numpy(), obj)
 
 
 def test_dataset_recompute_mode(rcd):
