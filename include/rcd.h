@@ -46,7 +46,13 @@ typedef enum { RCD_F32 = 0, RCD_BF16 = 1 } rcd_dtype;
 typedef enum {
     RCD_MODE_AUTO = 0,     /* stored if the workspace can hold at least one class's S, else recompute */
     RCD_MODE_STORED = 1,   /* build S per class once, stream it in every gain sweep */
-    RCD_MODE_RECOMPUTE = 2 /* never store S: rebuild its tiles from X inside every gain sweep */
+    RCD_MODE_RECOMPUTE = 2, /* never store S: rebuild its tiles from X inside every gain sweep */
+    RCD_MODE_INCREMENTAL = 3 /* stored S, and every block's gains are kept current from step to step:
+                                taking v* into block k changes cur_k on D = {j : S(j,v*) > cur_k(j)} only, and
+                                gain_k(v) moves by sum_{j in D} [max(0,S(j,v)-new_j) - max(0,S(j,v)-old_j)],
+                                so a step reads |D| rows of S instead of one per candidate.  Same Algorithm 1,
+                                same tie rules; gains are carried in double.  rcd_partition_class takes this
+                                route when the environment variable RCD_INCREMENTAL is 1. */
 } rcd_mode;
 
 /*

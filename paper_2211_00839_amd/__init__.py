@@ -28,4 +28,5 @@ BF16 = 1
 MODE_AUTO = 0
 MODE_STORED = 1
 MODE_RECOMPUTE = 2
+MODE_INCREMENTAL = 3
 MAX_K = 16

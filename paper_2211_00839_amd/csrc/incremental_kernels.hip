@@ -1,0 +1,348 @@
+// Class greedy with incrementally maintained gains (stored similarity), for gfx950.
+//
+// Algorithm 1's loop is unchanged: j* = the non-full block of least f, v* = the unassigned
+// sample of largest gain f(A_j* u {v}) - f(A_j*), lowest index on ties.  What changes is how a
+// block's gains are kept current.  With the facility-location function of Section 4,
+//     gain_k(v) = sum_j max(0, S(j,v) - cur_k(j)),     cur_k(j) = max_{a in A_k} S(j,a),
+// taking v* into block k raises cur_k only on D = { j : S(j,v*) > cur_k(j) }, so
+//     gain_k(v) += sum_{j in D} [ max(0, S(j,v) - new_j) - max(0, S(j,v) - old_j) ]      for every v.
+// D is the whole class for a block's first sample and shrinks quickly after that (a dozen rows
+// after a few hundred samples on mixture data), so a step reads |D| rows of S instead of one row
+// per candidate.  The gains start as the column sums of S (all cur = 0).
+//
+// Precision.  A gain shrinks by five orders of magnitude over a run while being updated thousands
+// of times, so the running values are kept in double: every term is a difference of two fp32 numbers
+// taken in double, hence exact, and the sums are good to ~1e-13 relative.  Two candidates with
+// identical columns go through identical operations in identical order, so exact ties stay exact
+// and the lowest index wins them.
+//
+// Layout (inside the buffers every class owns; see inc_* below): gains G[k][v] in sample order
+// (a taken sample's entries are set to a large negative sentinel), and per block the list of the
+// changed j in ascending order with their old coverage values (the new ones are in cur).
+// Included by rcd_lib.hip after greedy_kernels.hip.
+#include <hip/hip_runtime.h>
+#include "rcd_state.h"
+
+namespace {
+
+constexpr double INC_TAKEN = -1.0e300;      // gain entry of a sample that is no longer a candidate
+constexpr double INC_LIVE_ABOVE = -1.0e299; // anything above this is a live candidate's gain
+constexpr int INC_SMALL = 32;               // update lists up to this length are applied by the step loop itself
+
+__device__ __forceinline__ double *inc_gains(const RcdClass &st) { return reinterpret_cast<double *>(st.part); }
+__device__ __forceinline__ float *inc_dold(const RcdClass &st) { return st.part + 2 * (size_t)st.K * st.ld; }
+__device__ __forceinline__ int32_t *inc_dlist(const RcdClass &st) { return reinterpret_cast<int32_t *>(st.gain); }
+
+// one term of the update, exact in double
+__device__ __forceinline__ double inc_term(float s, float new_c, float old_c)
+{
+    const double d = (double)s;
+    return fmax(d - (double)new_c, 0.0) - fmax(d - (double)old_c, 0.0);
+}
+
+__device__ __forceinline__ double wave_sum_f64(double a)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off);   // partners add the same two numbers
+    return a;
+}
+
+} // namespace
+
+// Initial gains: G[k][v] = sum_j S(j,v) for every block (all coverage vectors are 0), one wave
+// per candidate row of M, double accumulation in a fixed order.  grid = (ceil(max n / 4), ncls).
+extern "C" __global__ void __launch_bounds__(256)
+rcd_k_inc_init(const RcdClass *__restrict__ classes)
+{
+    const RcdClass &st = classes[blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= st.n) return;
+    const int ld = st.ld, K = st.K;
+    const gcf32 row = (gcf32)st.M + (size_t)v * ld + lane * 4;
+    double a = 0.0;
+    for (int s = 0; s < ld; s += 256) {
+        const f32x4 m = *(gcf32x4)(row + s);
+        a += ((double)m.x + (double)m.y) + ((double)m.z + (double)m.w);
+    }
+    a = wave_sum_f64(a);
+    if (lane < K) inc_gains(st)[(size_t)lane * ld + v] = a;
+}
+
+// Apply the pending update lists: for every class, every block with a pending list, every tile of
+// 256 samples v:  G[k][v] += sum over the list of the term above.  The workgroup's 4 waves take a
+// quarter of the list each (in list order) and their sums are added in wave order.
+// grid = (max ld / 256, K, ncls).
+extern "C" __global__ void __launch_bounds__(256)
+rcd_k_inc_update(const RcdClass *__restrict__ classes)
+{
+    __shared__ double sums[4][4][64];
+    const RcdClass &st = classes[blockIdx.z];
+    const int slot = blockIdx.y;
+    if (st.done || slot >= st.nneed) return;
+    const int k = st.need[slot];
+    const int nd = st.dcount[k];
+    const int ld = st.ld;
+    const int v0 = blockIdx.x * 256;
+    if (nd <= 0 || v0 >= ld) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const cci32 dl = (cci32)(inc_dlist(st) + (size_t)k * ld);
+    const ccf32 dold = (ccf32)(inc_dold(st) + (size_t)k * ld);
+    const ccf32 cur = (ccf32)(st.cur + (size_t)k * ld);
+    const gcf32 M = (gcf32)st.M + v0 + lane * 4;
+    const int q = (nd + 3) >> 2;
+    const int e0 = wave * q, e1 = min(nd, e0 + q);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    int e = e0;
+    constexpr int U = 8;      // rows in flight per wave
+    for (; e + U <= e1; e += U) {
+        f32x4 m[U];
+        float cn[U], co[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = dl[e + u];
+            cn[u] = cur[j];
+            co[u] = dold[e + u];
+            m[u] = *(gcf32x4)(M + (size_t)j * ld);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc[0] += inc_term(m[u].x, cn[u], co[u]);
+            acc[1] += inc_term(m[u].y, cn[u], co[u]);
+            acc[2] += inc_term(m[u].z, cn[u], co[u]);
+            acc[3] += inc_term(m[u].w, cn[u], co[u]);
+        }
+    }
+    for (; e < e1; ++e) {
+        const int j = dl[e];
+        const float cn = cur[j], co = dold[e];
+        const f32x4 m = *(gcf32x4)(M + (size_t)j * ld);
+        acc[0] += inc_term(m.x, cn, co);
+        acc[1] += inc_term(m.y, cn, co);
+        acc[2] += inc_term(m.z, cn, co);
+        acc[3] += inc_term(m.w, cn, co);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sums[wave][c][lane] = acc[c];
+    __syncthreads();
+    if (wave == 0) {
+        double *g = inc_gains(st) + (size_t)k * ld + v0 + lane * 4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double t = ((sums[0][c][lane] + sums[1][c][lane]) + sums[2][c][lane]) + sums[3][c][lane];
+            g[c] += t;
+        }
+    }
+}
+
+namespace {
+
+struct IncShared {
+    RcdClass d;
+    double wbest[RCD_STEP_THREADS / 64];
+    int wv[RCD_STEP_THREADS / 64];
+    int wcount[RCD_STEP_THREADS / 64];
+    int sj[INC_SMALL];
+    float sold[INC_SMALL], snew[INC_SMALL];
+};
+
+// better of two (gain, sample) pairs: larger gain, then the smaller sample index
+__device__ __forceinline__ void inc_better(double &g, int &v, double og, int ov)
+{
+    if (og > g || (og == g && ov < v)) { g = og; v = ov; }
+}
+
+} // namespace
+
+// Greedy steps of one class, one workgroup of 1024 threads, for as long as the block that is next
+// in turn has current gains.  A step: argmin block (LDS), argmax over that block's gains (one scan),
+// bookkeeping, coverage update from row v* of M with the ordered list of changed j, and then either
+// the gain update applied right here (short list) or the list left pending for rcd_k_inc_update
+// (long list; the block sits out until then, the others go on).  plans[0].ndone counts finished classes.
+extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
+rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
+{
+    constexpr int NT = RCD_STEP_THREADS, NW = NT / 64;
+    __shared__ IncShared sh;
+    RcdClass &st = classes[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    {
+        const gci32 g = (gci32)reinterpret_cast<const int32_t *>(&st);
+        int32_t *l = reinterpret_cast<int32_t *>(&sh.d);
+        for (int i = tid; i < (int)(sizeof(RcdClass) / 4); i += NT) l[i] = g[i];
+    }
+    __syncthreads();
+    RcdClass &d = sh.d;
+    if (d.done) {
+        if (tid == 0) st.nneed = 0;
+        return;
+    }
+    const long long tick0 = wall_clock64();
+    const int K = d.K, n = d.n, ld = d.ld, total = d.total;
+    // the update launch that ran since the last call brought these blocks' gains up to date
+    if (tid < d.nneed) d.valid[d.need[tid]] = 1;
+    __syncthreads();
+    double *G = inc_gains(d);
+    int32_t *dlist = inc_dlist(d);
+    float *dold = inc_dold(d);
+    const gcf32 M = (gcf32)d.M;
+    const int seg = ((ld + NW - 1) / NW + 255) / 256 * 256;     // j range of a wave in the coverage update
+
+    int nR = d.nR, t = d.t, done = 0;
+    const int t0 = t;
+    long long useful = 0, entries = 0, computed = 0, sweeps = 0;
+    for (;;) {
+        if (t >= total) { done = 1; break; }
+        int js = -1;
+        double fbest = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (d.cnt[k] >= d.cap[k]) continue;
+            const double fk = d.f[k];
+            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
+        }
+        if (js < 0) { done = 1; break; }
+        if (!d.valid[js]) break;
+
+        // ---- argmax over the block's gains
+        const double *g = G + (size_t)js * ld;
+        double best = INC_LIVE_ABOVE;
+        int bv = 0x7fffffff;
+        for (int v = tid; v < n; v += NT) {
+            const double x = g[v];
+            if (x > best) { best = x; bv = v; }      // ascending v per thread: the first maximum stays
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const double og = __shfl_xor(best, off);
+            const int ov = __shfl_xor(bv, off);
+            inc_better(best, bv, og, ov);
+        }
+        if (lane == 0) { sh.wbest[wave] = best; sh.wv[wave] = bv; }
+        __syncthreads();
+        best = sh.wbest[0];
+        bv = sh.wv[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) inc_better(best, bv, sh.wbest[w], sh.wv[w]);
+        const int vstar = bv;
+        if (vstar >= n) { done = 1; break; }          // no candidate left (cannot happen while t < total <= n)
+
+        // ---- bookkeeping and outputs
+        if (tid == 0) {
+            d.cnt[js] += 1;
+            d.f[js] += best;
+            const int oi = d.out_index ? d.out_index[vstar] : vstar;
+            d.assign_out[oi] = js;
+            if (d.order_out) d.order_out[oi] = t;
+        }
+        if (tid < K) G[(size_t)tid * ld + vstar] = INC_TAKEN;
+
+        // ---- coverage update cur_js(j) = max(cur_js(j), S(j, v*)) and the ordered list of changed j
+        const gcf32 row = M + (size_t)vstar * ld;
+        float *cur = d.cur + (size_t)js * ld;
+        const int j_begin = wave * seg, j_end = min(ld, j_begin + seg);
+        int cnt = 0;
+        for (int s = j_begin + lane * 4; s < j_end; s += 256) {
+            const f32x4 m = *(gcf32x4)(row + s);
+            const f32x4 c = *(const f32x4 *)(cur + s);
+            cnt += (m.x > c.x) + (m.y > c.y) + (m.z > c.z) + (m.w > c.w);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
+        __syncthreads();           // everyone has read wbest / wv of this step
+        if (lane == 0) sh.wcount[wave] = cnt;
+        __syncthreads();
+        int base = 0, nd = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const int c = sh.wcount[w];
+            if (w < wave) base += c;
+            nd += c;
+        }
+        int32_t *dl = dlist + (size_t)js * ld;
+        float *dol = dold + (size_t)js * ld;
+        for (int s = j_begin + lane * 4; s < j_end; s += 256) {
+            const f32x4 m = *(gcf32x4)(row + s);
+            const f32x4 c = *(const f32x4 *)(cur + s);
+            const bool ch[4] = {m.x > c.x, m.y > c.y, m.z > c.z, m.w > c.w};
+            const int mine = ch[0] + ch[1] + ch[2] + ch[3];
+            int incl = mine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            int pos = base + incl - mine;
+            const float mv[4] = {m.x, m.y, m.z, m.w}, cv[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (ch[q]) {
+                    dl[pos] = s + q;
+                    dol[pos] = cv[q];
+                    if (nd <= INC_SMALL) { sh.sj[pos] = s + q; sh.sold[pos] = cv[q]; sh.snew[pos] = mv[q]; }
+                    ++pos;
+                }
+            if (mine) {
+                f32x4 r;
+                r.x = fmaxf(c.x, m.x); r.y = fmaxf(c.y, m.y); r.z = fmaxf(c.z, m.z); r.w = fmaxf(c.w, m.w);
+                *(f32x4 *)(cur + s) = r;
+            }
+            base += __shfl(incl, 63);
+        }
+        entries += (long long)nd * n;
+        computed += nR - 1;
+        if (nd > INC_SMALL) {
+            // long list: left to the update launch, the block sits out until then
+            if (tid == 0) { d.valid[js] = 0; d.dcount[js] = nd; }
+            sweeps += 1;
+        } else if (nd > 0) {
+            __syncthreads();       // the short list is complete in LDS
+            double *gj = G + (size_t)js * ld;
+            for (int v0 = tid * 4; v0 < ld; v0 += NT * 4) {
+                double acc[4] = {0.0, 0.0, 0.0, 0.0};
+                for (int e = 0; e < nd; ++e) {
+                    const f32x4 m = *(gcf32x4)(M + (size_t)sh.sj[e] * ld + v0);
+                    const float cn = sh.snew[e], co = sh.sold[e];
+                    acc[0] += inc_term(m.x, cn, co);
+                    acc[1] += inc_term(m.y, cn, co);
+                    acc[2] += inc_term(m.z, cn, co);
+                    acc[3] += inc_term(m.w, cn, co);
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) gj[v0 + c] += acc[c];
+            }
+        }
+        useful += nR;
+        nR -= 1;
+        ++t;
+        __syncthreads();           // the step's writes (gains, lists, LDS state) are in place
+    }
+
+    // ---- the descriptor: which blocks wait for the update launch, the state, the counters
+    __syncthreads();
+    if (tid == 0) {
+        int nneed = 0;
+        if (!done)
+            for (int k = 0; k < K; ++k)
+                if (d.cnt[k] < d.cap[k] && !d.valid[k]) d.need[nneed++] = k;
+        d.nneed = nneed;
+        d.stat_sweeps += sweeps;
+        d.stat_entries += entries;
+        d.stat_computed += computed;
+        d.stat_steps += t - t0;
+        d.stat_useful += useful;
+        d.nR = nR;
+        d.t = t;
+        d.done = done;
+        d.stat_ticks += wall_clock64() - tick0;
+        if (done) __hip_atomic_fetch_add(&plans[0].ndone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    {
+        constexpr int first = (int)(offsetof(RcdClass, nR) / 4);
+        gi32 g = (gi32)reinterpret_cast<int32_t *>(&st);
+        const int32_t *l = reinterpret_cast<const int32_t *>(&sh.d);
+        for (int i = first + tid; i < (int)(sizeof(RcdClass) / 4); i += NT) g[i] = l[i];
+    }
+}

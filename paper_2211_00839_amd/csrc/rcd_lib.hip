@@ -16,6 +16,7 @@
 #include "similarity_kernels.hip"
 #include "split_kernels.hip"
 #include "recompute_kernels.hip"
+#include "incremental_kernels.hip"
 
 static_assert(RCD_KMAX == RCD_MAX_K, "public and internal block limits differ");
 
@@ -262,6 +263,8 @@ struct Lane {
     int slot = 0;            // which pinned progress slots are this lane's
     int ncls = 0, rounds = 16, items_ub = 0, round_no = 0;
     bool recompute = false, fused = false, prof = false, finished = false;
+    bool incremental = false;   // stored S with incrementally maintained gains
+    dim3 update_grid;
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
     size_t round_rc_lds = 0;   // dynamic LDS of the recompute sweep (fast path only)
     void (*apply_rc)(RcdClass *, int) = nullptr;
@@ -329,7 +332,15 @@ struct Lane {
         // a group is homogeneous: all stored, or all recomputed from the same X
         const RcdClass &first = g->host[0];
         recompute = first.mode == RCD_MODE_RECOMPUTE;
-        if (!recompute) {
+        incremental = !recompute && first.incremental != 0;
+        if (incremental) {
+            int max_ld = 0;
+            for (const RcdClass &c : g->host) max_ld = std::max(max_ld, c.ld);
+            update_grid = dim3((unsigned)(max_ld / 256), (unsigned)first.K, (unsigned)ncls);
+            // initial gains = column sums of S: every coverage vector is 0
+            hipLaunchKernelGGL(rcd_k_inc_init, dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls), dim3(256), 0, stream,
+                               (const RcdClass *)g->classes_dev);
+        } else if (!recompute) {
             RCD_TRY(sweep_setup());
             const std::vector<RcdWg> map = deal_workgroups(g->host, std::min(sweep_target, RCD_MAX_SWEEP_WGS));
             sweep_wgs = (int)map.size();
@@ -339,6 +350,9 @@ struct Lane {
         // step loop number 1 (the bootstrap) and its apply; step loop r+2 follows round r's sweep
         if (recompute)
             hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev);
+        else if (incremental)
+            hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                               g->plan_dev);
         else
             hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                g->plan_dev);
@@ -395,13 +409,18 @@ struct Lane {
             if (recompute)
                 hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), round_rc_lds, stream, g->classes_dev, g->plan_dev,
                                    buf);
+            else if (incremental)
+                hipLaunchKernelGGL(rcd_k_inc_update, update_grid, dim3(256), 0, stream, (const RcdClass *)g->classes_dev);
             else
                 hipLaunchKernelGGL(rcd_k_sweep_rows, dim3(sweep_wgs), dim3(RCD_SWEEP_THREADS),
                                    RCD_SWEEP_LDS_FLOATS * 4, stream, (const RcdClass *)g->classes_dev,
                                    (const RcdWg *)g->wgmap_dev);
             ++round_no;
             if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
-            if (!recompute)
+            if (incremental)
+                hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                                   g->plan_dev);
+            else if (!recompute)
                 hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                    g->plan_dev);
             else if (!fused)
@@ -847,6 +866,9 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     if (!carve_class(cv, c, n, K, cap_host, stored)) return RCD_ERR_WORKSPACE;
     c.assign_out = assign_dev;
     c.order_out = order_dev;
+    c.incremental = stored && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0;
+    if (c.incremental)
+        for (int k = 0; k < K; ++k) c.valid[k] = 1;      // the initial gains (column sums) are current
     HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
     if (stored) {
         hipLaunchKernelGGL(rcd_k_copy_check, dim3((unsigned)(c.ld / 32), (unsigned)((n + 31) / 32)), dim3(256), 0,
@@ -872,7 +894,9 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
     if (L < 1 || !r_host || !obj_host) return RCD_ERR_INVALID_ARG;
     if (L > 8192) return RCD_ERR_UNSUPPORTED;
     if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
-    if (mode != RCD_MODE_AUTO && mode != RCD_MODE_STORED && mode != RCD_MODE_RECOMPUTE) return RCD_ERR_UNSUPPORTED;
+    if (mode != RCD_MODE_AUTO && mode != RCD_MODE_STORED && mode != RCD_MODE_RECOMPUTE && mode != RCD_MODE_INCREMENTAL)
+        return RCD_ERR_UNSUPPORTED;
+    const bool incremental = mode == RCD_MODE_INCREMENTAL || (mode != RCD_MODE_RECOMPUTE && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0);
     if (d < 1 || ld_x < d || !(sigma2 > 0.f) || !std::isfinite(sigma2)) return RCD_ERR_INVALID_ARG;
     for (int k = 0; k < K; ++k)
         if (r_host[k] < 1) return RCD_ERR_BAD_CAPACITY;
@@ -968,6 +992,9 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
                 c.assign_out = assign_dev;
                 c.order_out = order_dev;
                 c.out_index = idx + offset[l];
+                c.incremental = stored && incremental;
+                if (c.incremental)
+                    for (int k = 0; k < K; ++k) c.valid[k] = 1;      // the initial gains (column sums) are current
                 if (stored) {
                     float *sq = gc.take<float>((size_t)count[l]);
                     if (gc.fail) return RCD_ERR_WORKSPACE;

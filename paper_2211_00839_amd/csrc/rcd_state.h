@@ -39,6 +39,7 @@ struct RcdClass {
     int32_t row_align;   // rows per chunk are a multiple of this
     float exp_scale;     // -log2(e) / (2 sigma^2)
     int32_t target_items;       // sweep workgroups this class should be split into
+    int32_t incremental;        // stored S: gains are kept current by update lists instead of sweeps
     // ---- evolving
     int32_t nR;          // unassigned samples = live columns
     int32_t t;           // steps taken
@@ -51,6 +52,7 @@ struct RcdClass {
     int32_t cnt[RCD_KMAX];
     int32_t cap[RCD_KMAX];
     int32_t valid[RCD_KMAX];
+    int32_t dcount[RCD_KMAX];   // incremental gains: length of block k's pending update list
     double f[RCD_KMAX];  // running f(A_k): sum of accepted gains
     // decisions of the last step loop, consumed by the apply kernel of the same round
     int32_t apply_round; // number of step loops run so far = round the lists belong to
