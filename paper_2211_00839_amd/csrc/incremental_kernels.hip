@@ -27,7 +27,7 @@ namespace {
 
 constexpr double INC_TAKEN = -1.0e300;      // gain entry of a sample that is no longer a candidate
 constexpr double INC_LIVE_ABOVE = -1.0e299; // anything above this is a live candidate's gain
-constexpr int INC_SMALL = 32;               // update lists up to this length are applied by the step loop itself
+constexpr int INC_SMALL = 512;              // most rows of an update list that the step loop applies itself (LDS copy of the list)
 
 __device__ __forceinline__ double *inc_gains(const RcdClass &st) { return reinterpret_cast<double *>(st.part); }
 __device__ __forceinline__ float *inc_dold(const RcdClass &st) { return st.part + 2 * (size_t)st.K * st.ld; }
@@ -159,9 +159,11 @@ __device__ __forceinline__ void inc_better(double &g, int &v, double og, int ov)
 // in turn has current gains.  A step: argmin block (LDS), argmax over that block's gains (one scan),
 // bookkeeping, coverage update from row v* of M with the ordered list of changed j, and then either
 // the gain update applied right here (short list) or the list left pending for rcd_k_inc_update
-// (long list; the block sits out until then, the others go on).  plans[0].ndone counts finished classes.
+// (long list, more than small_bytes of rows; the block sits out until then, the others go on).  At most
+// max_steps steps per call.
+// plans[0].ndone counts finished classes.
 extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
-rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
+rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int max_steps, int small_bytes)
 {
     constexpr int NT = RCD_STEP_THREADS, NW = NT / 64;
     __shared__ IncShared sh;
@@ -189,12 +191,16 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
     float *dold = inc_dold(d);
     const gcf32 M = (gcf32)d.M;
     const int seg = ((ld + NW - 1) / NW + 255) / 256 * 256;     // j range of a wave in the coverage update
+    // lists up to this many rows are applied right here: one workgroup reads a few MB in the time a
+    // trip through the update launch takes, so the limit is a number of bytes
+    const int small = max(4, min(INC_SMALL, small_bytes / (ld * 4)));
 
     int nR = d.nR, t = d.t, done = 0;
     const int t0 = t;
     long long useful = 0, entries = 0, computed = 0, sweeps = 0;
     for (;;) {
         if (t >= total) { done = 1; break; }
+        if (t - t0 >= max_steps) break;      // a class that waits for the update launch waits for every class's call
         int js = -1;
         double fbest = 0.0;
         for (int k = 0; k < K; ++k) {
@@ -280,7 +286,7 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
                 if (ch[q]) {
                     dl[pos] = s + q;
                     dol[pos] = cv[q];
-                    if (nd <= INC_SMALL) { sh.sj[pos] = s + q; sh.sold[pos] = cv[q]; sh.snew[pos] = mv[q]; }
+                    if (nd <= small) { sh.sj[pos] = s + q; sh.sold[pos] = cv[q]; sh.snew[pos] = mv[q]; }
                     ++pos;
                 }
             if (mine) {
@@ -292,7 +298,7 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
         }
         entries += (long long)nd * n;
         computed += nR - 1;
-        if (nd > INC_SMALL) {
+        if (nd > small) {
             // long list: left to the update launch, the block sits out until then
             if (tid == 0) { d.valid[js] = 0; d.dcount[js] = nd; }
             sweeps += 1;
@@ -301,13 +307,21 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans)
             double *gj = G + (size_t)js * ld;
             for (int v0 = tid * 4; v0 < ld; v0 += NT * 4) {
                 double acc[4] = {0.0, 0.0, 0.0, 0.0};
-                for (int e = 0; e < nd; ++e) {
-                    const f32x4 m = *(gcf32x4)(M + (size_t)sh.sj[e] * ld + v0);
-                    const float cn = sh.snew[e], co = sh.sold[e];
-                    acc[0] += inc_term(m.x, cn, co);
-                    acc[1] += inc_term(m.y, cn, co);
-                    acc[2] += inc_term(m.z, cn, co);
-                    acc[3] += inc_term(m.w, cn, co);
+                // eight rows in flight at a time (the loads of a batch are independent of one another)
+                for (int e0 = 0; e0 < nd; e0 += 8) {
+                    f32x4 m[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (e0 + u < nd) m[u] = *(gcf32x4)(M + (size_t)sh.sj[e0 + u] * ld + v0);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (e0 + u < nd) {
+                            const float cn = sh.snew[e0 + u], co = sh.sold[e0 + u];
+                            acc[0] += inc_term(m[u].x, cn, co);
+                            acc[1] += inc_term(m[u].y, cn, co);
+                            acc[2] += inc_term(m[u].z, cn, co);
+                            acc[3] += inc_term(m[u].w, cn, co);
+                        }
                 }
 #pragma unroll
                 for (int c = 0; c < 4; ++c) gj[v0 + c] += acc[c];

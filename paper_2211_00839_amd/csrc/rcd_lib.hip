@@ -265,6 +265,8 @@ struct Lane {
     bool recompute = false, fused = false, prof = false, finished = false;
     bool incremental = false;   // stored S with incrementally maintained gains
     dim3 update_grid;
+    int inc_small_bytes = 512 << 10;   // update lists up to this many bytes of rows are applied by the step loop itself
+    int inc_max_steps = 64;     // steps per class and launch: a class that waits for the update launch waits for the whole lane
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
     size_t round_rc_lds = 0;   // dynamic LDS of the recompute sweep (fast path only)
     void (*apply_rc)(RcdClass *, int) = nullptr;
@@ -333,6 +335,8 @@ struct Lane {
         const RcdClass &first = g->host[0];
         recompute = first.mode == RCD_MODE_RECOMPUTE;
         incremental = !recompute && first.incremental != 0;
+        inc_max_steps = env_int("RCD_INC_STEPS", ncls > 1 ? 32 : 4096, 1, 1 << 20);
+        inc_small_bytes = env_int("RCD_INC_SMALL_KB", 512, 1, 1 << 20) * 1024;
         if (incremental) {
             int max_ld = 0;
             for (const RcdClass &c : g->host) max_ld = std::max(max_ld, c.ld);
@@ -352,7 +356,7 @@ struct Lane {
             hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev);
         else if (incremental)
             hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
-                               g->plan_dev);
+                               g->plan_dev, inc_max_steps, inc_small_bytes);
         else
             hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                g->plan_dev);
@@ -419,7 +423,7 @@ struct Lane {
             if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
             if (incremental)
                 hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
-                                   g->plan_dev);
+                                   g->plan_dev, inc_max_steps, inc_small_bytes);
             else if (!recompute)
                 hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                    g->plan_dev);
