@@ -152,3 +152,75 @@ def test_large_class_full_size_window_recompute_equals_stored(rcd):
     cols = S[:, torch.from_numpy(members).cuda()].max(dim=1).values.double().sum().item()
     assert abs(f1[0] - cols) <= 1e-4 * cols
     print(f"  stats {s1}", flush=True)
+
+
+# ------------------------------------------------------------------ incremental-gain route at full size
+@pytest.mark.parametrize("name", ["cifar10", "hetero8"])
+def test_full_size_incremental_workloads(rcd, name):
+    print(f"full size {name}, incremental gains", flush=True)
+    ds = si.make_dataset(si.WORKLOADS[name])
+    Xd, assign, order, obj = run_full(rcd, ds, rcd.MODE_INCREMENTAL)
+    stats = rcd.last_stats()
+    assert stats["steps"] == ds.X.shape[0]
+    rng = np.random.default_rng(21)
+    for c in range(ds.L):
+        check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=14, sim_tol=1e-5, referee=c in (1, 5, 8))
+    print(f"  stats {stats}", flush=True)
+    # the sweep route on the same data takes the same decisions (up to near-ties, which show in the objectives)
+    _, a2, o2, f2 = run_full(rcd, ds, rcd.MODE_STORED)
+    print("  agreement with the sweep route:", np.mean(assign == a2), flush=True)
+    assert np.allclose(obj, f2, rtol=1e-4)
+
+
+def test_full_size_cifar100_incremental_every_step(rcd):
+    print("full size cifar100, incremental gains", flush=True)
+    ds = si.make_dataset(si.WORKLOADS["cifar100"])
+    Xd, assign, order, obj = run_full(rcd, ds, rcd.MODE_INCREMENTAL)
+    rng = np.random.default_rng(22)
+    for c in range(ds.L):
+        res = check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=500, sim_tol=1e-5, referee=c % 10 == 3)
+        if res:
+            assert res["checked"] == 500
+
+
+def test_large_class_one_full_class_incremental(rcd):
+    # one whole class of the large workload (50 000 x 2048 bf16, K = 8, its real quotas): similarity
+    # stored (10 GB), all 50 000 steps by the incremental route; the oracle referees sampled steps
+    # on the same S and the objectives come from the definition
+    print("large workload, one full class, all 50 000 steps, incremental gains", flush=True)
+    w = si.WORKLOADS["large"]
+    X = si.make_class(seed=w.seed, n=w.n_c, d=w.d, G=w.G, dtype="bf16")
+    Xd = dev(X)
+    S = rcd.similarity(Xd, float(w.d))
+    cap = oracle.quota(w.n_c, w.r)
+    assert cap.tolist() == [2083, 2083, 4166, 4166, 6251, 6250, 8334, 16667]
+    import os
+    old = os.environ.get("RCD_INCREMENTAL")
+    os.environ["RCD_INCREMENTAL"] = "1"
+    try:
+        a, o, f = rcd.partition_class(S=S, cap=cap)
+    finally:
+        if old is None:
+            del os.environ["RCD_INCREMENTAL"]
+        else:
+            os.environ["RCD_INCREMENTAL"] = old
+    stats = rcd.last_stats()
+    print(f"  stats {stats}", flush=True)
+    a, o = a.cpu().numpy(), o.cpu().numpy()
+    assert stats["steps"] == w.n_c
+    assert np.bincount(a, minlength=8).tolist() == cap.tolist()
+    assert np.array_equal(np.sort(o), np.arange(w.n_c))
+    # objectives from the definition, on the device (max over the block's columns, summed in double)
+    for k in (0, 7):
+        members = torch.from_numpy(np.flatnonzero(a == k)).cuda()
+        ref = 0.0
+        for lo in range(0, w.n_c, 5000):        # row chunks keep the gathered slab small
+            ref += S[lo:lo + 5000][:, members].max(dim=1).values.double().sum().item()
+        assert abs(f[k] - ref) <= 1e-4 * ref
+    # sampled lock step by the oracle on the same S
+    Sh = S.cpu().numpy()
+    del S
+    steps = [0, 1, 7, 8, 9, 1000, 25000, 49998, 49999]
+    res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps)
+    print(f"  referee {res}", flush=True)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
