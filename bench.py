@@ -120,6 +120,33 @@ def extra_kernels(rcd, si, torch):
     return res
 
 
+def large_workload(rcd, si, torch):
+    """The whole large-class workload (20 classes x 50 000 samples, d = 2048 bf16, K = 8) by the
+    incremental route with every class's similarity stored (200 GB of workspace): 1 000 000 greedy steps."""
+    w = si.WORKLOADS["large"]
+    try:
+        ds = si.make_dataset(w)
+        X = torch.from_numpy(ds.X.view(np.int16)).cuda().view(torch.bfloat16)
+        labels = torch.from_numpy(ds.labels).cuda()
+        _, full = rcd.dataset_workspace_bytes(len(ds.labels), ds.L, w.n_c, len(ds.r), rcd.MODE_INCREMENTAL)
+        free, _ = torch.cuda.mem_get_info()
+        if full > free * 0.95:
+            return {"skipped": f"needs {full / 1e9:.0f} GB of workspace, {free / 1e9:.0f} GB free"}
+        ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, rcd.MODE_INCREMENTAL, ws)
+        torch.cuda.synchronize()
+        sec = time.perf_counter() - t0
+        st = rcd.last_stats()
+        return {"workload": describe(w, ds), "route": "RCD_MODE_INCREMENTAL, every class's S stored",
+                "partition_wall_time_s": sec, "greedy_steps": st["steps"],
+                "useful_evals_per_s": st["useful_evals"] / sec, "similarity_entries_read": st["entries_streamed"],
+                "workspace_GB": full / 1e9, "runs_timed": 1}
+    except Exception as e:       # e.g. not enough device or host memory on another box
+        return {"skipped": repr(e)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +155,7 @@ def main():
     ap.add_argument("--workload", default="cifar10")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the large-class similarity / recompute-sweep lines")
+    ap.add_argument("--no-large", action="store_true", help="skip the whole large-class workload (200 GB of workspace)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (known traffic) so that rocprofv3 byte counters can be scaled")
     ap.add_argument("--scale", default="", help="L,n_c,d override for quick runs (not a valid bench line)")
@@ -216,6 +244,30 @@ def main():
         with open(traffic_file) as fh:
             roofline["traffic"] = json.load(fh).get("hbm_bytes_per_launch")
 
+    # the same step by the incremental-gain route (same Algorithm 1, same answers: gains are moved by the
+    # rows of S whose coverage changed instead of rebuilt by sweeps)
+    def step_inc():
+        return rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, rcd.MODE_INCREMENTAL, ws)
+
+    step_inc()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        a_inc, o_inc, f_inc = step_inc()
+    torch.cuda.synchronize()
+    inc_ms = 1e3 * (time.perf_counter() - t2) / max(args.steps, 1)
+    istats = rcd.last_stats()
+    incremental = {
+        "route": "RCD_MODE_INCREMENTAL on the same workload, same timing protocol",
+        "ms_per_step": inc_ms,
+        "value": istats["useful_evals"] / (inc_ms * 1e-3),
+        "unit": "gain-evals/s",
+        "similarity_entries_read": istats["entries_streamed"],
+        "similarity_entries_read_by_sweeps": stats["entries_streamed"],
+        "kernel_launches": istats["launches"],
+        "same_assignment_as_sweep_route": bool(torch.equal(a_inc, assign)),
+    }
+
     out = {
         "metric": "marginal-gain evals/sec (gain evaluations Algorithm 1 consumes / whole-job wall time)",
         "value": value,
@@ -240,9 +292,13 @@ def main():
         "time_split_ms": {"similarity": prof["similarity_ms"], "sweep": prof["sweep_ms"], "steps": prof["steps_ms"],
                           "apply": prof["apply_ms"], "instrumented_step_total": prof_ms},
         "roofline": roofline,
+        "incremental_route": incremental,
     }
     if not args.scale and not args.no_extra:
+        del ws
         out["extra"] = extra_kernels(rcd, si, torch)
+        if not args.no_large:
+            out["extra"]["large_workload_incremental"] = large_workload(rcd, si, torch)
     if not args.no_cpu_baseline:
         n0 = int(counts[0])
         out["cpu_baseline"] = cpu_baseline(ds, budget_steps=min(96, n0))

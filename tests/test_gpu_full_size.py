@@ -224,3 +224,40 @@ def test_large_class_one_full_class_incremental(rcd):
     res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps)
     print(f"  referee {res}", flush=True)
     assert res["rc"] == 0 and res["checked"] == len(steps), res
+
+
+def test_large_workload_all_classes_incremental(rcd):
+    # the whole large workload: 20 classes x 50 000 samples, d = 2048 bf16, K = 8, every class's S stored
+    # (202 GB of workspace), one million steps; invariants for every class, one class refereed
+    print("large workload, all 20 classes, incremental gains", flush=True)
+    w = si.WORKLOADS["large"]
+    ds = si.make_dataset(w)
+    N = ds.X.shape[0]
+    _, full = rcd.dataset_workspace_bytes(N, ds.L, w.n_c, len(ds.r), rcd.MODE_INCREMENTAL)
+    free, _ = torch.cuda.mem_get_info()
+    if full > 0.95 * free:
+        pytest.skip(f"needs {full / 1e9:.0f} GB of workspace, {free / 1e9:.0f} GB free on this device")
+    Xd, assign, order, obj = run_full(rcd, ds, rcd.MODE_INCREMENTAL)
+    stats = rcd.last_stats()
+    print(f"  stats {stats}", flush=True)
+    assert stats["steps"] == N
+    cap = oracle.quota(w.n_c, ds.r)
+    for c in range(ds.L):
+        idx = np.flatnonzero(ds.labels == c)
+        assert np.bincount(assign[idx], minlength=len(ds.r)).tolist() == cap.tolist()
+        assert np.array_equal(np.sort(order[idx]), np.arange(w.n_c))
+    # class 13: the library's own similarity of the class (gathered rows), sampled steps refereed on it
+    idx = np.flatnonzero(ds.labels == 13)
+    S = rcd.similarity(Xd, ds.sigma2, row_index=dev(idx.astype(np.int32)))
+    a, o = assign[idx], order[idx]
+    members = torch.from_numpy(np.flatnonzero(a == 7)).cuda()
+    ref = 0.0
+    for lo in range(0, w.n_c, 5000):
+        ref += S[lo:lo + 5000][:, members].max(dim=1).values.double().sum().item()
+    assert abs(obj[13, 7] - ref) <= 1e-4 * ref
+    Sh = S.cpu().numpy()
+    del S
+    steps = [0, 3, 8, 500, 30000, 49999]
+    res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps)
+    print(f"  referee of class 13: {res}", flush=True)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
