@@ -61,6 +61,12 @@ def _load():
     lib.oracle_lockstep.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, dbl, vp, vp]
     lib.oracle_bruteforce.restype = i64
     lib.oracle_bruteforce.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.oracle_f_gc.restype = dbl
+    lib.oracle_f_gc.argtypes = [vp, i64, i64, vp, i64]
+    lib.oracle_partition_class_gc.restype = i64
+    lib.oracle_partition_class_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.oracle_lockstep_gc.restype = i32
+    lib.oracle_lockstep_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, dbl, vp, vp]
     lib.oracle_partition_dataset.restype = i32
     lib.oracle_partition_dataset.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, i32, dbl, vp, vp, vp]
     _lib = lib
@@ -109,10 +115,12 @@ def quota(n_l: int, r) -> np.ndarray:
     return cap
 
 
-def f_value(S, members) -> float:
+def f_value(S, members, objective: str = "fl") -> float:
+    """f(A) from the definition: facility location ("fl") or graph cut ("gc")."""
     S = _sim_matrix(S)
     mem = np.ascontiguousarray(members, dtype=np.int32)
-    return float(_load().oracle_f(_ptr(S), S.shape[1], S.shape[0], _ptr(mem), len(mem)))
+    fn = _load().oracle_f if objective == "fl" else _load().oracle_f_gc
+    return float(fn(_ptr(S), S.shape[1], S.shape[0], _ptr(mem), len(mem)))
 
 
 def gain_row(S, cov, assign=None) -> np.ndarray:
@@ -127,9 +135,9 @@ def gain_row(S, cov, assign=None) -> np.ndarray:
     return g
 
 
-def partition_class(S, cap, trace: bool = False):
-    """Algorithm 1 on one class.  Returns dict(assign, order, obj, fsum, steps
-    [, tr_block, tr_elem, tr_gain])."""
+def partition_class(S, cap, trace: bool = False, objective: str = "fl"):
+    """Algorithm 1 on one class with the facility-location ("fl") or graph-cut ("gc") function.
+    Returns dict(assign, order, obj, fsum, steps[, tr_block, tr_elem, tr_gain])."""
     S = _sim_matrix(S)
     n = S.shape[0]
     cap = np.ascontiguousarray(cap, dtype=np.int64)
@@ -143,9 +151,9 @@ def partition_class(S, cap, trace: bool = False):
         tb = np.full(max(n, 1), -1, dtype=np.int32)
         te = np.full(max(n, 1), -1, dtype=np.int32)
         tg = np.zeros(max(n, 1), dtype=np.float64)
-    steps = _load().oracle_partition_class(
-        _ptr(S), S.shape[1], n, K, _ptr(cap), _ptr(assign), _ptr(order), _ptr(obj), _ptr(fsum),
-        _ptr(tb), _ptr(te), _ptr(tg))
+    fn = _load().oracle_partition_class if objective == "fl" else _load().oracle_partition_class_gc
+    steps = fn(_ptr(S), S.shape[1], n, K, _ptr(cap), _ptr(assign), _ptr(order), _ptr(obj), _ptr(fsum),
+               _ptr(tb), _ptr(te), _ptr(tg))
     if steps < 0:
         raise ValueError("oracle_partition_class rejected its arguments")
     out = dict(assign=assign, order=order, obj=obj, fsum=fsum, steps=int(steps))
@@ -154,7 +162,7 @@ def partition_class(S, cap, trace: bool = False):
     return out
 
 
-def lockstep(S, cap, order, assign, rel_tol: float = 1e-5, check=None):
+def lockstep(S, cap, order, assign, rel_tol: float = 1e-5, check=None, objective: str = "fl"):
     """Referee a foreign trace against Algorithm 1 (see oracle_lockstep in the C
     file).  Returns dict(rc, checked, exact, near_block, near_elem, violations,
     first_violation, worst_elem_gap, worst_block_gap)."""
@@ -171,9 +179,9 @@ def lockstep(S, cap, order, assign, rel_tol: float = 1e-5, check=None):
         chk[idx[idx < steps]] = 1
     stats = np.zeros(6, dtype=np.int64)
     worst = np.zeros(2, dtype=np.float64)
-    rc = _load().oracle_lockstep(_ptr(S), S.shape[1], n, len(cap), _ptr(cap), _ptr(order),
-                                 _ptr(assign), steps, _ptr(chk), float(rel_tol), _ptr(stats),
-                                 _ptr(worst))
+    fn = _load().oracle_lockstep if objective == "fl" else _load().oracle_lockstep_gc
+    rc = fn(_ptr(S), S.shape[1], n, len(cap), _ptr(cap), _ptr(order), _ptr(assign), steps, _ptr(chk),
+            float(rel_tol), _ptr(stats), _ptr(worst))
     return dict(rc=int(rc), checked=int(stats[0]), exact=int(stats[1]), near_block=int(stats[2]),
                 near_elem=int(stats[3]), violations=int(stats[4]), first_violation=int(stats[5]),
                 worst_elem_gap=float(worst[0]), worst_block_gap=float(worst[1]), steps=steps)

@@ -563,3 +563,255 @@ int oracle_partition_dataset(const void *X, int dtype, int64_t N, int64_t d, int
     free(cap); free(idx);
     return rc;
 }
+
+/* ======================================================================================
+ * Graph cut, the paper's second submodular function (Section 4, "Submodular functions"):
+ *   f(A) = sum over v in V_l \ A of  sum over v' in A of  sim(v, v').
+ * V_l \ A is every class member outside A, samples given to other blocks included.
+ * Algorithm 1 is unchanged (argmin-f block, GreedyStep = the unassigned v of largest
+ * f(A u {v}) - f(A), lowest index on ties, a block leaves J once its quota is met).
+ * f is not monotone: a marginal value can be negative, and the sample with the largest one
+ * is still taken, because the quotas have to be met (Algorithm 1 has no sign test).
+ * Readings: f(empty) = 0 (empty sum); sim is used as printed, S[v][a] = sim(v, a).
+ * ====================================================================================== */
+
+/* f(A) from the definition; members[m] lists A. */
+double oracle_f_gc(const float *S, int64_t lds, int64_t n, const int32_t *members, int64_t m)
+{
+    if (m <= 0)
+        return 0.0;
+    char *in = (char *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!in)
+        return 0.0;
+    for (int64_t a = 0; a < m; ++a)
+        in[members[a]] = 1;
+    double total = 0.0;
+    for (int64_t v = 0; v < n; ++v) {
+        if (in[v])
+            continue;
+        for (int64_t a = 0; a < m; ++a)
+            total += (double)S[v * lds + members[a]];
+    }
+    free(in);
+    return total;
+}
+
+/* f(A u {u}) - f(A) for the block whose members are the v with assign[v] == k:
+ * u leaves V \ A, so its own terms sum_{a in A} sim(u, a) go, and u enters A, so the
+ * terms sum_{v outside A, v != u} sim(v, u) come in.  (tests pin this against the
+ * definition above evaluated twice.) */
+static double gain_of_gc(const float *S, int64_t lds, int64_t n, const int32_t *assign, int k, int64_t u)
+{
+    double g = 0.0;
+    for (int64_t v = 0; v < n; ++v) {
+        if (v == u)
+            continue;
+        if (assign[v] == k)
+            g -= (double)S[u * lds + v];
+        else
+            g += (double)S[v * lds + u];
+    }
+    return g;
+}
+
+/* Same contract as oracle_partition_class, with the graph-cut f. */
+int64_t oracle_partition_class_gc(const float *S, int64_t lds, int64_t n, int K, const int64_t *cap,
+                                  int32_t *assign, int32_t *order, double *obj, double *fsum,
+                                  int32_t *tr_block, int32_t *tr_elem, double *tr_gain)
+{
+    if (!S || !cap || !assign || n < 0 || K < 1 || lds < n)
+        return -1;
+    int64_t total_cap = 0;
+    for (int k = 0; k < K; ++k) {
+        if (cap[k] < 0)
+            return -1;
+        total_cap += cap[k];
+    }
+    if (total_cap > n)
+        return -1;
+    double *f = (double *)calloc((size_t)K, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)K, sizeof(int64_t));
+    char *open = (char *)malloc((size_t)K);
+    if (!f || !cnt || !open) {
+        free(f); free(cnt); free(open);
+        return -1;
+    }
+    memset(open, 1, (size_t)K);
+    for (int64_t v = 0; v < n; ++v) {
+        assign[v] = -1;
+        if (order)
+            order[v] = -1;
+    }
+    int64_t remaining = n;
+    int n_open = K;
+    int64_t t = 0;
+    while (remaining > 0 && n_open > 0) {
+        int js = -1;
+        for (int k = 0; k < K; ++k) {
+            if (!open[k])
+                continue;
+            if (js < 0 || f[k] < f[js])
+                js = k;
+        }
+        if (cnt[js] < cap[js]) {
+            int64_t vs = -1;
+            double best = 0.0;
+            for (int64_t v = 0; v < n; ++v) {
+                if (assign[v] >= 0)
+                    continue;
+                double g = gain_of_gc(S, lds, n, assign, js, v);
+                if (vs < 0 || g > best) {
+                    best = g;
+                    vs = v;
+                }
+            }
+            assign[vs] = js;
+            if (order)
+                order[vs] = (int32_t)t;
+            if (tr_block) tr_block[t] = js;
+            if (tr_elem) tr_elem[t] = (int32_t)vs;
+            if (tr_gain) tr_gain[t] = best;
+            cnt[js] += 1;
+            f[js] += best;
+            remaining -= 1;
+            t += 1;
+        } else {
+            open[js] = 0;
+            n_open -= 1;
+        }
+    }
+    if (fsum)
+        for (int k = 0; k < K; ++k)
+            fsum[k] = f[k];
+    if (obj) {
+        int32_t *mem = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));
+        if (!mem) {
+            free(f); free(cnt); free(open);
+            return -1;
+        }
+        for (int k = 0; k < K; ++k) {
+            int64_t m = 0;
+            for (int64_t v = 0; v < n; ++v)
+                if (assign[v] == k)
+                    mem[m++] = (int32_t)v;
+            obj[k] = oracle_f_gc(S, lds, n, mem, m);
+        }
+        free(mem);
+    }
+    free(f); free(cnt); free(open);
+    return t;
+}
+
+/* Lock-step referee for the graph-cut f: same contract and statistics as oracle_lockstep.
+ * Marginal values can be negative or zero, so the element gap is taken relative to the
+ * larger magnitude of the two values compared. */
+int oracle_lockstep_gc(const float *S, int64_t lds, int64_t n, int K, const int64_t *cap,
+                       const int32_t *order, const int32_t *assign, int64_t steps,
+                       const uint8_t *check, double rel_tol, int64_t *stats, double *worst)
+{
+    if (!S || !cap || !order || !assign || !stats || n < 0 || K < 1 || steps < 0 || steps > n)
+        return -1;
+    int32_t *elem_at = (int32_t *)malloc((size_t)(steps > 0 ? steps : 1) * sizeof(int32_t));
+    int32_t *state = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));   /* block so far, -1 */
+    double *f = (double *)calloc((size_t)K, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)K, sizeof(int64_t));
+    if (!elem_at || !state || !f || !cnt) {
+        free(elem_at); free(state); free(f); free(cnt);
+        return -1;
+    }
+    int rc = 0;
+    for (int64_t t = 0; t < steps; ++t)
+        elem_at[t] = -1;
+    for (int64_t v = 0; v < n; ++v) {
+        state[v] = -1;
+        int32_t o = order[v];
+        if (o < 0) {
+            if (assign[v] >= 0) rc = -1;
+            continue;
+        }
+        if (o >= steps || elem_at[o] >= 0 || assign[v] < 0 || assign[v] >= K) {
+            rc = -1;
+            continue;
+        }
+        elem_at[o] = (int32_t)v;
+    }
+    for (int64_t t = 0; t < steps; ++t)
+        if (elem_at[t] < 0)
+            rc = -1;
+    for (int i = 0; i < 6; ++i)
+        stats[i] = 0;
+    stats[5] = -1;
+    if (worst) {
+        worst[0] = 0.0;
+        worst[1] = 0.0;
+    }
+    if (rc != 0) {
+        free(elem_at); free(state); free(f); free(cnt);
+        return -1;
+    }
+    for (int64_t t = 0; t < steps; ++t) {
+        int32_t v_ext = elem_at[t];
+        int k_ext = assign[v_ext];
+        int violated = 0;
+        if (cnt[k_ext] >= cap[k_ext])
+            violated = 1;
+        double g_ext = gain_of_gc(S, lds, n, state, k_ext, v_ext);
+        if (!violated && (!check || check[t])) {
+            int near_block = 0, near_elem = 0;
+            int js = -1;
+            for (int k = 0; k < K; ++k) {
+                if (cnt[k] >= cap[k])
+                    continue;
+                if (js < 0 || f[k] < f[js])
+                    js = k;
+            }
+            if (js != k_ext) {
+                double gap = fabs(f[k_ext] - f[js]);
+                double scale = fmax(fabs(f[k_ext]), fabs(f[js]));
+                double rel = scale > 0.0 ? gap / scale : 0.0;
+                if (worst && rel > worst[1]) worst[1] = rel;
+                if (rel <= rel_tol)
+                    near_block = 1;
+                else
+                    violated = 1;
+            }
+            int64_t vs = -1;
+            double best = 0.0;
+            for (int64_t v = 0; v < n; ++v) {
+                if (state[v] >= 0)
+                    continue;
+                double g = gain_of_gc(S, lds, n, state, k_ext, v);
+                if (vs < 0 || g > best) {
+                    best = g;
+                    vs = v;
+                }
+            }
+            if (vs != v_ext) {
+                double scale = fmax(fabs(best), fabs(g_ext));
+                double rel = scale > 0.0 ? (best - g_ext) / scale : 0.0;
+                if (worst && rel > worst[0]) worst[0] = rel;
+                if (rel <= rel_tol)
+                    near_elem = 1;
+                else
+                    violated = 1;
+            }
+            stats[0] += 1;
+            if (!violated) {
+                if (!near_block && !near_elem) stats[1] += 1;
+                if (near_block) stats[2] += 1;
+                if (near_elem) stats[3] += 1;
+            }
+        }
+        if (violated) {
+            stats[4] += 1;
+            if (stats[5] < 0)
+                stats[5] = t;
+            rc = 1;
+        }
+        state[v_ext] = k_ext;
+        cnt[k_ext] += 1;
+        f[k_ext] += g_ext;
+    }
+    free(elem_at); free(state); free(f); free(cnt);
+    return rc;
+}
