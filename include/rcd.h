@@ -130,6 +130,31 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
                           int32_t *assign_dev, int32_t *order_dev, double *obj_host,
                           void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/*
+ * The same two calls with the graph-cut function, the other submodular function
+ * Section 4 names for Algorithm 1:
+ *     f(A) = sum_{v in V_l \ A} sum_{a in A} S(v, a)
+ * (the similarity mass between a block and the rest of its class).  Algorithm 1
+ * itself, the quotas and both tie rules are unchanged.  f is submodular but not
+ * monotone: a marginal value f(A u {v}) - f(A) = sum_{u != v} S(u,v) - 2 sum_{a in A} S(v,a)
+ * can be negative, and the largest one is taken all the same, since the quotas
+ * are constraints.  S must be symmetric (it is read by rows).  Marginal values are
+ * carried in double from exact fp32 entries, so candidates that tie exactly in
+ * exact arithmetic tie here.  S is always stored: the class call takes S_dev
+ * (n x n, ld_s, entries in [0,1]), the data-set call builds S per class like
+ * RCD_MODE_STORED.  Workspace: the RCD_MODE_STORED sizes.  obj_host receives
+ * f(A_k) as the sum of the accepted marginal values.  Arguments, outputs, error
+ * codes and synchronisation as for rcd_partition_class / rcd_partition_dataset.
+ */
+int rcd_partition_class_graph_cut(const float *S_dev, int64_t ld_s, int64_t n, int K, const int64_t *cap_host,
+                                  int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                                  void *workspace_dev, size_t workspace_bytes, void *stream);
+int rcd_partition_dataset_graph_cut(const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
+                                    const int32_t *labels_dev, int L, const int32_t *r_host, int K,
+                                    float sigma2,
+                                    int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                                    void *workspace_dev, size_t workspace_bytes, void *stream);
+
 /* Workspace sizes in bytes (multiples of 256; the pointer must be 256-byte aligned).
  * rcd_class_workspace_bytes: what rcd_partition_class / rcd_gain_sweep need for a
  *   class of n samples (stored mode includes a private n x ld copy of S).

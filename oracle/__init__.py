@@ -66,7 +66,7 @@ def _load():
     lib.oracle_partition_class_gc.restype = i64
     lib.oracle_partition_class_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.oracle_lockstep_gc.restype = i32
-    lib.oracle_lockstep_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, dbl, vp, vp]
+    lib.oracle_lockstep_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, dbl, dbl, vp, vp]
     lib.oracle_partition_dataset.restype = i32
     lib.oracle_partition_dataset.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, i32, dbl, vp, vp, vp]
     _lib = lib
@@ -162,9 +162,9 @@ def partition_class(S, cap, trace: bool = False, objective: str = "fl"):
     return out
 
 
-def lockstep(S, cap, order, assign, rel_tol: float = 1e-5, check=None, objective: str = "fl"):
+def lockstep(S, cap, order, assign, rel_tol: float = 1e-5, check=None, objective: str = "fl", abs_tol: float = 0.0):
     """Referee a foreign trace against Algorithm 1 (see oracle_lockstep in the C
-    file).  Returns dict(rc, checked, exact, near_block, near_elem, violations,
+    file; abs_tol is the graph-cut referee's absolute element window).  Returns dict(rc, checked, exact, near_block, near_elem, violations,
     first_violation, worst_elem_gap, worst_block_gap)."""
     S = _sim_matrix(S)
     n = S.shape[0]
@@ -180,8 +180,9 @@ def lockstep(S, cap, order, assign, rel_tol: float = 1e-5, check=None, objective
     stats = np.zeros(6, dtype=np.int64)
     worst = np.zeros(2, dtype=np.float64)
     fn = _load().oracle_lockstep if objective == "fl" else _load().oracle_lockstep_gc
+    tol = (float(rel_tol),) if objective == "fl" else (float(rel_tol), float(abs_tol))
     rc = fn(_ptr(S), S.shape[1], n, len(cap), _ptr(cap), _ptr(order), _ptr(assign), steps, _ptr(chk),
-            float(rel_tol), _ptr(stats), _ptr(worst))
+            *tol, _ptr(stats), _ptr(worst))
     return dict(rc=int(rc), checked=int(stats[0]), exact=int(stats[1]), near_block=int(stats[2]),
                 near_elem=int(stats[3]), violations=int(stats[4]), first_violation=int(stats[5]),
                 worst_elem_gap=float(worst[0]), worst_block_gap=float(worst[1]), steps=steps)

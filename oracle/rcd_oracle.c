@@ -704,10 +704,13 @@ int64_t oracle_partition_class_gc(const float *S, int64_t lds, int64_t n, int K,
 
 /* Lock-step referee for the graph-cut f: same contract and statistics as oracle_lockstep.
  * Marginal values can be negative or zero, so the element gap is taken relative to the
- * larger magnitude of the two values compared. */
+ * larger magnitude of the two values compared.  A marginal value here is a difference of two
+ * sums of similarities, so when the trace was made on a slightly different S (entries off by
+ * e each) its values are off by up to n*e however small they are themselves: abs_tol (>= 0,
+ * 0 for a trace made on this very S) widens the element window by that absolute amount. */
 int oracle_lockstep_gc(const float *S, int64_t lds, int64_t n, int K, const int64_t *cap,
                        const int32_t *order, const int32_t *assign, int64_t steps,
-                       const uint8_t *check, double rel_tol, int64_t *stats, double *worst)
+                       const uint8_t *check, double rel_tol, double abs_tol, int64_t *stats, double *worst)
 {
     if (!S || !cap || !order || !assign || !stats || n < 0 || K < 1 || steps < 0 || steps > n)
         return -1;
@@ -790,7 +793,7 @@ int oracle_lockstep_gc(const float *S, int64_t lds, int64_t n, int K, const int6
                 double scale = fmax(fabs(best), fabs(g_ext));
                 double rel = scale > 0.0 ? (best - g_ext) / scale : 0.0;
                 if (worst && rel > worst[0]) worst[0] = rel;
-                if (rel <= rel_tol)
+                if (rel <= rel_tol || best - g_ext <= abs_tol)
                     near_elem = 1;
                 else
                     violated = 1;

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     partition_class,
+    partition_class_graph_cut,
     partition_dataset,
     profile,
     profile_read,

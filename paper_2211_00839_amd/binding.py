@@ -14,7 +14,8 @@ _lib = None
 
 EXPORTS = [
     "rcd_similarity", "rcd_similarity_workspace_bytes", "rcd_quota", "rcd_gain_sweep",
-    "rcd_partition_class", "rcd_partition_dataset", "rcd_class_workspace_bytes",
+    "rcd_partition_class", "rcd_partition_dataset", "rcd_partition_class_graph_cut",
+    "rcd_partition_dataset_graph_cut", "rcd_class_workspace_bytes",
     "rcd_dataset_workspace_bytes", "rcd_strerror", "rcd_last_hip_error", "rcd_last_stats",
     "rcd_profile", "rcd_profile_read",
 ]
@@ -56,6 +57,10 @@ def load_library():
     lib.rcd_partition_dataset.restype = i32
     lib.rcd_partition_dataset.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, i32, f32, i32, vp, vp, vp, vp, sz, vp]
     lib.rcd_class_workspace_bytes.restype = sz
+    lib.rcd_partition_class_graph_cut.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.rcd_partition_class_graph_cut.restype = i32
+    lib.rcd_partition_dataset_graph_cut.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, i32, f32, vp, vp, vp, vp, sz, vp]
+    lib.rcd_partition_dataset_graph_cut.restype = i32
     lib.rcd_class_workspace_bytes.argtypes = [i64, i32, i32]
     lib.rcd_dataset_workspace_bytes.restype = i32
     lib.rcd_dataset_workspace_bytes.argtypes = [i64, i32, i64, i32, i32, vp, vp]
@@ -202,8 +207,31 @@ def partition_class(S=None, cap=None, X=None, sigma2: float = 1.0, workspace=Non
     return assign, order, obj
 
 
-def partition_dataset(X, labels, L: int, r, sigma2: float, mode: int = 0, workspace=None, want_order: bool = True):
-    """Whole data set.  Returns (assign int32[N] device, order or None, obj float64[L, K] numpy)."""
+def partition_class_graph_cut(S, cap, workspace=None, want_order: bool = True):
+    """One class of Algorithm 1 with the graph-cut function, on a stored symmetric S.
+    Returns (assign int32[n] device, order int32[n] device or None, obj float64[K] numpy)."""
+    import torch
+
+    lib = load_library()
+    cap = np.ascontiguousarray(cap, dtype=np.int64)
+    K = len(cap)
+    n = S.shape[0]
+    assert S.dtype == torch.float32 and S.stride(1) == 1
+    assign = torch.empty(n, dtype=torch.int32, device=S.device)
+    order = torch.empty(n, dtype=torch.int32, device=S.device) if want_order else None
+    obj = np.zeros(K, dtype=np.float64)
+    if workspace is None:
+        workspace = _workspace(lib.rcd_class_workspace_bytes(n, K, 1), S.device)
+    _check(lib.rcd_partition_class_graph_cut(_dev_ptr(S), S.stride(0), n, K, _np_ptr(cap), _dev_ptr(assign),
+                                             _dev_ptr(order), _np_ptr(obj), _dev_ptr(workspace), workspace.numel(),
+                                             _stream()))
+    return assign, order, obj
+
+
+def partition_dataset(X, labels, L: int, r, sigma2: float, mode: int = 0, workspace=None, want_order: bool = True,
+                      graph_cut: bool = False):
+    """Whole data set.  Returns (assign int32[N] device, order or None, obj float64[L, K] numpy).
+    graph_cut=True runs Algorithm 1 with the graph-cut function (stored S; mode is not used)."""
     import torch
 
     lib = load_library()
@@ -216,6 +244,12 @@ def partition_dataset(X, labels, L: int, r, sigma2: float, mode: int = 0, worksp
     obj = np.zeros((L, K), dtype=np.float64)
     if workspace is None:
         raise RcdError(5, "partition_dataset needs a workspace tensor (see dataset_workspace_bytes)")
+    if graph_cut:
+        _check(lib.rcd_partition_dataset_graph_cut(_dev_ptr(X), _dtype_code(X), N, d, X.stride(0), _dev_ptr(labels),
+                                                   int(L), _np_ptr(r), K, float(sigma2), _dev_ptr(assign),
+                                                   _dev_ptr(order), _np_ptr(obj), _dev_ptr(workspace),
+                                                   workspace.numel(), _stream()))
+        return assign, order, obj
     _check(lib.rcd_partition_dataset(_dev_ptr(X), _dtype_code(X), N, d, X.stride(0), _dev_ptr(labels), int(L),
                                      _np_ptr(r), K, float(sigma2), int(mode), _dev_ptr(assign), _dev_ptr(order),
                                      _np_ptr(obj), _dev_ptr(workspace), workspace.numel(), _stream()))

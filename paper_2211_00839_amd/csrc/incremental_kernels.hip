@@ -360,3 +360,147 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
         for (int i = first + tid; i < (int)(sizeof(RcdClass) / 4); i += NT) g[i] = l[i];
     }
 }
+
+// ======================================================================================
+// Graph cut, the second submodular function of Section 4:
+//     f(A) = sum_{v in V_l \ A} sum_{v' in A} sim(v, v').
+// With a symmetric S, f(A u {u}) - f(A) = colsum(u) - S(u,u) - 2 sum_{a in A} S(u,a): a block's
+// marginal values start as the column sums without the diagonal and taking v* lowers every one of
+// them by 2 S(v, v*), which is row v* of M.  So the gains are always current, a step is one scan
+// and one row, and the whole class runs in the step loop below.  Same Algorithm 1, same tie
+// rules; f is not monotone, marginal values go negative and the largest one is still taken (the
+// quotas have to be met).  Gains are carried in double (sums of fp32 numbers taken in double are
+// exact), so exact ties stay exact.  Uses the gain array of the incremental route.
+// ======================================================================================
+
+// G[k][v] = sum_j S(j,v) - S(v,v) for every block.  grid = (ceil(max n / 4), ncls).
+extern "C" __global__ void __launch_bounds__(256)
+rcd_k_gc_init(const RcdClass *__restrict__ classes)
+{
+    const RcdClass &st = classes[blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= st.n) return;
+    const int ld = st.ld, K = st.K;
+    const gcf32 row = (gcf32)st.M + (size_t)v * ld + lane * 4;
+    double a = 0.0;
+    for (int s = 0; s < ld; s += 256) {
+        const f32x4 m = *(gcf32x4)(row + s);
+        a += ((double)m.x + (double)m.y) + ((double)m.z + (double)m.w);
+    }
+    // whole row first, diagonal off afterwards: two samples with identical rows get identical values
+    a = wave_sum_f64(a) - (double)((gcf32)st.M)[(size_t)v * ld + v];
+    if (lane < K) inc_gains(st)[(size_t)lane * ld + v] = a;
+}
+
+// Greedy steps of one class with the graph-cut function, one workgroup of 1024 threads, up to
+// max_steps steps per call.  plans[0].ndone counts finished classes.
+extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
+rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int max_steps)
+{
+    constexpr int NT = RCD_STEP_THREADS, NW = NT / 64;
+    __shared__ IncShared sh;
+    RcdClass &st = classes[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    {
+        const gci32 g = (gci32)reinterpret_cast<const int32_t *>(&st);
+        int32_t *l = reinterpret_cast<int32_t *>(&sh.d);
+        for (int i = tid; i < (int)(sizeof(RcdClass) / 4); i += NT) l[i] = g[i];
+    }
+    __syncthreads();
+    RcdClass &d = sh.d;
+    if (d.done) return;
+    const long long tick0 = wall_clock64();
+    const int K = d.K, n = d.n, ld = d.ld, total = d.total;
+    double *G = inc_gains(d);
+    const gcf32 M = (gcf32)d.M;
+    int nR = d.nR, t = d.t, done = 0;
+    const int t0 = t;
+    long long useful = 0;
+    for (;;) {
+        if (t >= total) { done = 1; break; }
+        if (t - t0 >= max_steps) break;
+        int js = -1;
+        double fbest = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (d.cnt[k] >= d.cap[k]) continue;
+            const double fk = d.f[k];
+            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
+        }
+        if (js < 0) { done = 1; break; }
+        // ---- argmax over the block's marginal values (they may be negative)
+        double *g = G + (size_t)js * ld;
+        double best = INC_LIVE_ABOVE;
+        int bv = 0x7fffffff;
+        for (int v = tid; v < n; v += NT) {
+            const double x = g[v];
+            if (x > best) { best = x; bv = v; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const double og = __shfl_xor(best, off);
+            const int ov = __shfl_xor(bv, off);
+            inc_better(best, bv, og, ov);
+        }
+        if (lane == 0) { sh.wbest[wave] = best; sh.wv[wave] = bv; }
+        __syncthreads();
+        best = sh.wbest[0];
+        bv = sh.wv[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) inc_better(best, bv, sh.wbest[w], sh.wv[w]);
+        const int vstar = bv;
+        if (vstar >= n) { done = 1; break; }
+        __syncthreads();           // everyone has read wbest / wv and the block state of this step
+        if (tid == 0) {
+            d.cnt[js] += 1;
+            d.f[js] += best;
+            const int oi = d.out_index ? d.out_index[vstar] : vstar;
+            d.assign_out[oi] = js;
+            if (d.order_out) d.order_out[oi] = t;
+        }
+        // ---- every marginal value of the block drops by 2 S(v, v*); v* leaves every block's candidates
+        const gcf32 row = M + (size_t)vstar * ld;
+        for (int v0 = tid * 4; v0 < ld; v0 += NT * 4) {
+            const f32x4 m = *(gcf32x4)(row + v0);
+            g[v0] -= 2.0 * (double)m.x;
+            g[v0 + 1] -= 2.0 * (double)m.y;
+            g[v0 + 2] -= 2.0 * (double)m.z;
+            g[v0 + 3] -= 2.0 * (double)m.w;
+        }
+        __syncthreads();           // the row update is done before v* is struck out (both touch g[v*])
+        if (tid < K) G[(size_t)tid * ld + vstar] = INC_TAKEN;
+        useful += nR;
+        nR -= 1;
+        ++t;
+        __syncthreads();
+    }
+    __syncthreads();
+    if (tid == 0) {
+        d.nneed = 0;
+        d.stat_steps += t - t0;
+        d.stat_useful += useful;
+        d.stat_entries += (long long)(t - t0) * n;
+        d.nR = nR;
+        d.t = t;
+        d.done = done;
+        d.stat_ticks += wall_clock64() - tick0;
+        if (done) __hip_atomic_fetch_add(&plans[0].ndone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    {
+        constexpr int first = (int)(offsetof(RcdClass, nR) / 4);
+        gi32 gd = (gi32)reinterpret_cast<int32_t *>(&st);
+        const int32_t *l = reinterpret_cast<const int32_t *>(&sh.d);
+        for (int i = first + tid; i < (int)(sizeof(RcdClass) / 4); i += NT) gd[i] = l[i];
+    }
+}
+
+// obj[c][k] = f(A_k): the running sum of the accepted marginal values (exact to rounding in double).
+// grid = (1, ncls), K threads.
+extern "C" __global__ void rcd_k_gc_objective(const RcdClass *__restrict__ classes, double *__restrict__ obj, int Kstride)
+{
+    const RcdClass &st = classes[blockIdx.y];
+    const int k = threadIdx.x;
+    if (k < st.K) obj[(size_t)blockIdx.y * Kstride + k] = st.f[k];
+}

@@ -264,6 +264,8 @@ struct Lane {
     int ncls = 0, rounds = 16, items_ub = 0, round_no = 0;
     bool recompute = false, fused = false, prof = false, finished = false;
     bool incremental = false;   // stored S with incrementally maintained gains
+    bool graph_cut = false;     // graph-cut function: stored S, the step loop keeps its own gains current
+    int gc_max_steps = 4096;    // steps per class and launch (bounds a launch's duration)
     dim3 update_grid;
     int inc_small_bytes = 512 << 10;   // update lists up to this many bytes of rows are applied by the step loop itself
     int inc_max_steps = 64;     // steps per class and launch: a class that waits for the update launch waits for the whole lane
@@ -334,10 +336,16 @@ struct Lane {
         // a group is homogeneous: all stored, or all recomputed from the same X
         const RcdClass &first = g->host[0];
         recompute = first.mode == RCD_MODE_RECOMPUTE;
-        incremental = !recompute && first.incremental != 0;
+        graph_cut = first.objective == 1;
+        incremental = !recompute && !graph_cut && first.incremental != 0;
+        gc_max_steps = env_int("RCD_GC_STEPS", 4096, 1, 1 << 20);
         inc_max_steps = env_int("RCD_INC_STEPS", ncls > 1 ? 32 : 4096, 1, 1 << 20);
         inc_small_bytes = env_int("RCD_INC_SMALL_KB", 512, 1, 1 << 20) * 1024;
-        if (incremental) {
+        if (graph_cut) {
+            // initial marginal values = column sums of S without the diagonal
+            hipLaunchKernelGGL(rcd_k_gc_init, dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls), dim3(256), 0, stream,
+                               (const RcdClass *)g->classes_dev);
+        } else if (incremental) {
             int max_ld = 0;
             for (const RcdClass &c : g->host) max_ld = std::max(max_ld, c.ld);
             update_grid = dim3((unsigned)(max_ld / 256), (unsigned)first.K, (unsigned)ncls);
@@ -352,7 +360,10 @@ struct Lane {
             HIP_TRY(hipMemcpyAsync(g->wgmap_dev, map.data(), sizeof(RcdWg) * map.size(), hipMemcpyHostToDevice, stream));
         }
         // step loop number 1 (the bootstrap) and its apply; step loop r+2 follows round r's sweep
-        if (recompute)
+        if (graph_cut)
+            hipLaunchKernelGGL(rcd_k_gc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev,
+                               gc_max_steps);
+        else if (recompute)
             hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev);
         else if (incremental)
             hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
@@ -410,7 +421,9 @@ struct Lane {
         if (pe) (void)hipEventRecord((*pe)[0], stream);
         for (int r = 0; r < rounds; ++r) {
             const int buf = fused ? (round_no & 1) : 0;
-            if (recompute)
+            if (graph_cut)
+                ;   // nothing between the step loops: the gains are always current
+            else if (recompute)
                 hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), round_rc_lds, stream, g->classes_dev, g->plan_dev,
                                    buf);
             else if (incremental)
@@ -421,7 +434,10 @@ struct Lane {
                                    (const RcdWg *)g->wgmap_dev);
             ++round_no;
             if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
-            if (incremental)
+            if (graph_cut)
+                hipLaunchKernelGGL(rcd_k_gc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                                   g->plan_dev, gc_max_steps);
+            else if (incremental)
                 hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                    g->plan_dev, inc_max_steps, inc_small_bytes);
             else if (!recompute)
@@ -434,7 +450,7 @@ struct Lane {
             launch_apply(round_no + 1);
             if (pe) (void)hipEventRecord((*pe)[3 * r + 3], stream);
         }
-        launches += (!recompute || fused ? 2 : 3) * (int64_t)rounds;
+        launches += (graph_cut ? 1 : !recompute || fused ? 2 : 3) * (int64_t)rounds;
         hipError_t le = hipGetLastError();
         if (le != hipSuccess) {
             snprintf(g_hip_err, sizeof g_hip_err, "kernel launch -> %s", hipGetErrorString(le));
@@ -488,8 +504,12 @@ struct Lane {
             snprintf(g_hip_err, sizeof g_hip_err, "hipStreamSynchronize -> %s", hipGetErrorString(es));
             return RCD_ERR_HIP;
         }
-        hipLaunchKernelGGL(rcd_k_objective, dim3(g->K, ncls), dim3(256), 0, stream, (const RcdClass *)g->classes_dev,
-                           g->obj_dev, g->K);
+        if (graph_cut)
+            hipLaunchKernelGGL(rcd_k_gc_objective, dim3(1, ncls), dim3(64), 0, stream, (const RcdClass *)g->classes_dev,
+                               g->obj_dev, g->K);
+        else
+            hipLaunchKernelGGL(rcd_k_objective, dim3(g->K, ncls), dim3(256), 0, stream, (const RcdClass *)g->classes_dev,
+                               g->obj_dev, g->K);
         HIP_TRY(hipMemcpyAsync(g->host.data(), g->classes_dev, sizeof(RcdClass) * ncls, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
         for (const RcdClass &c : g->host) {
@@ -832,11 +852,12 @@ int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const flo
     return RCD_OK;
 }
 
-int rcd_partition_class(const float *S_dev, int64_t ld_s,
-                        const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
-                        int64_t n, int K, const int64_t *cap_host,
-                        int32_t *assign_dev, int32_t *order_dev, double *obj_host,
-                        void *workspace_dev, size_t workspace_bytes, void *stream_)
+// objective: 0 = facility location, 1 = graph cut (stored S only)
+static int partition_class_impl(int objective, const float *S_dev, int64_t ld_s,
+                                const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
+                                int64_t n, int K, const int64_t *cap_host,
+                                int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                                void *workspace_dev, size_t workspace_bytes, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
     reset_stats();
@@ -852,6 +873,7 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     if (n == 0) return RCD_OK;
     if (!assign_dev) return RCD_ERR_INVALID_ARG;
     const bool stored = S_dev != nullptr;
+    if (objective == 1 && !stored) return RCD_ERR_INVALID_ARG;
     if (stored) {
         if (ld_s < n) return RCD_ERR_INVALID_ARG;
         if (!stored_supported(n, K)) return RCD_ERR_UNSUPPORTED;
@@ -870,7 +892,8 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     if (!carve_class(cv, c, n, K, cap_host, stored)) return RCD_ERR_WORKSPACE;
     c.assign_out = assign_dev;
     c.order_out = order_dev;
-    c.incremental = stored && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0;
+    c.objective = objective;
+    c.incremental = stored && objective == 0 && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0;
     if (c.incremental)
         for (int k = 0; k < K; ++k) c.valid[k] = 1;      // the initial gains (column sums) are current
     HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
@@ -886,11 +909,30 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
     return RCD_OK;
 }
 
-int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
-                          const int32_t *labels_dev, int L, const int32_t *r_host, int K,
-                          float sigma2, int mode,
-                          int32_t *assign_dev, int32_t *order_dev, double *obj_host,
-                          void *workspace_dev, size_t workspace_bytes, void *stream_)
+int rcd_partition_class(const float *S_dev, int64_t ld_s,
+                        const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
+                        int64_t n, int K, const int64_t *cap_host,
+                        int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                        void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    return partition_class_impl(0, S_dev, ld_s, X_dev, dt, d, ld_x, sigma2, n, K, cap_host, assign_dev, order_dev,
+                                obj_host, workspace_dev, workspace_bytes, stream);
+}
+
+int rcd_partition_class_graph_cut(const float *S_dev, int64_t ld_s, int64_t n, int K, const int64_t *cap_host,
+                                  int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                                  void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    if (!S_dev && n > 0) return RCD_ERR_INVALID_ARG;
+    return partition_class_impl(1, S_dev, ld_s, nullptr, RCD_F32, 0, 0, 0.f, n, K, cap_host, assign_dev, order_dev,
+                                obj_host, workspace_dev, workspace_bytes, stream);
+}
+
+static int partition_dataset_impl(int objective, const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
+                                  const int32_t *labels_dev, int L, const int32_t *r_host, int K,
+                                  float sigma2, int mode,
+                                  int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                                  void *workspace_dev, size_t workspace_bytes, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
     reset_stats();
@@ -900,7 +942,8 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
     if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
     if (mode != RCD_MODE_AUTO && mode != RCD_MODE_STORED && mode != RCD_MODE_RECOMPUTE && mode != RCD_MODE_INCREMENTAL)
         return RCD_ERR_UNSUPPORTED;
-    const bool incremental = mode == RCD_MODE_INCREMENTAL || (mode != RCD_MODE_RECOMPUTE && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0);
+    const bool incremental = objective == 0 && (mode == RCD_MODE_INCREMENTAL ||
+                                                (mode != RCD_MODE_RECOMPUTE && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0));
     if (d < 1 || ld_x < d || !(sigma2 > 0.f) || !std::isfinite(sigma2)) return RCD_ERR_INVALID_ARG;
     for (int k = 0; k < K; ++k)
         if (r_host[k] < 1) return RCD_ERR_BAD_CAPACITY;
@@ -996,6 +1039,7 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
                 c.assign_out = assign_dev;
                 c.order_out = order_dev;
                 c.out_index = idx + offset[l];
+                c.objective = objective;
                 c.incremental = stored && incremental;
                 if (c.incremental)
                     for (int k = 0; k < K; ++k) c.valid[k] = 1;      // the initial gains (column sums) are current
@@ -1054,6 +1098,26 @@ int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64
     }
     HIP_TRY(hipStreamSynchronize(stream));
     return RCD_OK;
+}
+
+int rcd_partition_dataset(const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
+                          const int32_t *labels_dev, int L, const int32_t *r_host, int K,
+                          float sigma2, int mode,
+                          int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                          void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    return partition_dataset_impl(0, X_dev, dt, N, d, ld_x, labels_dev, L, r_host, K, sigma2, mode, assign_dev,
+                                  order_dev, obj_host, workspace_dev, workspace_bytes, stream);
+}
+
+int rcd_partition_dataset_graph_cut(const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
+                                    const int32_t *labels_dev, int L, const int32_t *r_host, int K,
+                                    float sigma2,
+                                    int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                                    void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    return partition_dataset_impl(1, X_dev, dt, N, d, ld_x, labels_dev, L, r_host, K, sigma2, RCD_MODE_STORED,
+                                  assign_dev, order_dev, obj_host, workspace_dev, workspace_bytes, stream);
 }
 
 } // extern "C"

@@ -40,6 +40,7 @@ struct RcdClass {
     float exp_scale;     // -log2(e) / (2 sigma^2)
     int32_t target_items;       // sweep workgroups this class should be split into
     int32_t incremental;        // stored S: gains are kept current by update lists instead of sweeps
+    int32_t objective;          // 0 = facility location, 1 = graph cut (stored S, its own step loop)
     // ---- evolving
     int32_t nR;          // unassigned samples = live columns
     int32_t t;           // steps taken
