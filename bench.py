@@ -53,6 +53,12 @@ def cpu_baseline(ds, budget_steps):
     t_greedy = time.perf_counter() - t0
     steps = out["steps"]
     evals = sum(n - t for t in range(steps))
+    # the graph-cut function on the same S: half the window (a marginal value walks a whole row here)
+    gwin = win // 2
+    t0 = time.perf_counter()
+    gout = oracle.partition_class(S0, gwin, objective="gc")
+    t_gc = time.perf_counter() - t0
+    gc_evals = sum(n - t for t in range(gout["steps"]))
     # whole-job estimate: every class pays its similarity build and n(n+1)/2 gain evaluations
     job_evals = ds.L * n * (n + 1) / 2
     job_time = ds.L * t_sim + job_evals / (evals / t_greedy)
@@ -66,6 +72,8 @@ def cpu_baseline(ds, budget_steps):
                    f"the window); value = whole-job rate extrapolated from both"),
         "greedy_window_evals_per_s": evals / t_greedy,
         "similarity_s_per_class": t_sim,
+        "graph_cut_window_evals_per_s": gc_evals / t_gc if t_gc > 0 else None,
+        "graph_cut_window": f"first {gout['steps']} steps of Algorithm 1 with the graph-cut function on the same S ({t_gc:.2f} s)",
         "host_cpus": os.cpu_count(),
     }
 
@@ -268,6 +276,32 @@ def main():
         "same_assignment_as_sweep_route": bool(torch.equal(a_inc, assign)),
     }
 
+    # Algorithm 1 with the graph-cut function of Section 4 on the same workload (stored S, same protocol)
+    def step_gc():
+        return rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, workspace=ws, graph_cut=True)
+
+    step_gc()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for _ in range(args.steps):
+        step_gc()
+    torch.cuda.synchronize()
+    gc_ms = 1e3 * (time.perf_counter() - t3) / max(args.steps, 1)
+    gstats = rcd.last_stats()
+    n_max = int(counts.max())
+    graph_cut = {
+        "route": "rcd_partition_dataset_graph_cut on the same workload, same timing protocol",
+        "ms_per_step": gc_ms,
+        "value": gstats["useful_evals"] / (gc_ms * 1e-3),
+        "unit": "gain-evals/s",
+        "greedy_steps": gstats["steps"],
+        "kernel_launches": gstats["launches"],
+        # a step reads the block's marginal values (8 B each), one row of S (4 B) and rewrites the values (16 B)
+        "bytes_per_greedy_step": 28 * n_max,
+        "us_per_greedy_step_in_loop": 10e-3 * gstats["step_ticks"] / max(gstats["steps"], 1) ,
+        "bound": "latency of one workgroup's step (scan, two barriers, one row): classes run side by side, one compute unit each",
+    }
+
     out = {
         "metric": "marginal-gain evals/sec (gain evaluations Algorithm 1 consumes / whole-job wall time)",
         "value": value,
@@ -293,6 +327,7 @@ def main():
                           "apply": prof["apply_ms"], "instrumented_step_total": prof_ms},
         "roofline": roofline,
         "incremental_route": incremental,
+        "graph_cut_route": graph_cut,
     }
     if not args.scale and not args.no_extra:
         del ws

@@ -599,7 +599,9 @@ double oracle_f_gc(const float *S, int64_t lds, int64_t n, const int32_t *member
 /* f(A u {u}) - f(A) for the block whose members are the v with assign[v] == k:
  * u leaves V \ A, so its own terms sum_{a in A} sim(u, a) go, and u enters A, so the
  * terms sum_{v outside A, v != u} sim(v, u) come in.  (tests pin this against the
- * definition above evaluated twice.) */
+ * definition above evaluated twice.)  Section 4's similarity is a function of the distance
+ * between two samples, hence symmetric: sim(v, u) is read from row u, S[u][v], so that a
+ * marginal value walks one row of S (callers pass a symmetric S). */
 static double gain_of_gc(const float *S, int64_t lds, int64_t n, const int32_t *assign, int k, int64_t u)
 {
     double g = 0.0;
@@ -609,7 +611,7 @@ static double gain_of_gc(const float *S, int64_t lds, int64_t n, const int32_t *
         if (assign[v] == k)
             g -= (double)S[u * lds + v];
         else
-            g += (double)S[v * lds + u];
+            g += (double)S[u * lds + v];
     }
     return g;
 }

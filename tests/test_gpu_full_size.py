@@ -261,3 +261,84 @@ def test_large_workload_all_classes_incremental(rcd):
     res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps)
     print(f"  referee of class 13: {res}", flush=True)
     assert res["rc"] == 0 and res["checked"] == len(steps), res
+
+
+def check_class_gc(rcd, ds, Xd, c, assign, order, obj, rng, n_steps):
+    idx = np.flatnonzero(ds.labels == c)
+    n = len(idx)
+    K = len(ds.r)
+    cap = oracle.quota(n, ds.r)
+    a, o = assign[idx], order[idx]
+    assert np.bincount(a, minlength=K).tolist() == cap.tolist()
+    assert np.array_equal(np.sort(o), np.arange(n))
+    S = rcd.similarity(Xd, ds.sigma2, row_index=dev(idx.astype(np.int32))).cpu().numpy()
+    steps = sampled_steps(n, rng, n_steps)
+    res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, check=steps, objective="gc")
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
+    mass = float(S.astype(np.float64).sum()) / K
+    for k in range(K):
+        ref_f = oracle.f_value(S, np.flatnonzero(a == k), "gc")
+        assert abs(obj[c, k] - ref_f) <= 1e-4 * ref_f + 1e-12 * mass
+    return res
+
+
+@pytest.mark.parametrize("name", ["cifar10", "hetero8"])
+def test_full_size_graph_cut_workloads(rcd, name):
+    print(f"full size {name}, graph-cut function", flush=True)
+    ds = si.make_dataset(si.WORKLOADS[name])
+    N = ds.X.shape[0]
+    counts = np.bincount(ds.labels, minlength=ds.L)
+    _, full = rcd.dataset_workspace_bytes(N, ds.L, int(counts.max()), len(ds.r), rcd.MODE_STORED)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    Xd = dev(ds.X)
+    assign, order, obj = rcd.partition_dataset(Xd, dev(ds.labels), ds.L, ds.r, ds.sigma2, workspace=ws, graph_cut=True)
+    del ws
+    stats = rcd.last_stats()
+    print(f"  stats {stats}", flush=True)
+    assert stats["steps"] == N
+    assign, order = assign.cpu().numpy(), order.cpu().numpy()
+    rng = np.random.default_rng(23)
+    for c in (1, 5, 8):
+        res = check_class_gc(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=10)
+        print(f"  class {c} referee {res}", flush=True)
+    for c in range(ds.L):
+        idx = np.flatnonzero(ds.labels == c)
+        assert np.bincount(assign[idx], minlength=len(ds.r)).tolist() == oracle.quota(len(idx), ds.r).tolist()
+
+
+def test_large_class_one_full_class_graph_cut(rcd):
+    # one whole class of the large workload (50 000 x 2048 bf16, K = 8, its real quotas), S stored, all
+    # 50 000 steps with the graph-cut function; invariants, objectives from the definition (on the device,
+    # in double), the first pick from its closed form, the oracle's referee on sampled steps
+    print("large workload, one full class, all 50 000 steps, graph-cut function", flush=True)
+    w = si.WORKLOADS["large"]
+    X = si.make_class(seed=w.seed, n=w.n_c, d=w.d, G=w.G, dtype="bf16")
+    S = rcd.similarity(dev(X), float(w.d))
+    cap = oracle.quota(w.n_c, w.r)
+    a, o, f = rcd.partition_class_graph_cut(S, cap)
+    stats = rcd.last_stats()
+    print(f"  stats {stats}", flush=True)
+    a, o = a.cpu().numpy(), o.cpu().numpy()
+    assert stats["steps"] == w.n_c
+    assert np.bincount(a, minlength=8).tolist() == cap.tolist()
+    assert np.array_equal(np.sort(o), np.arange(w.n_c))
+    # empty blocks: the marginal value of v is its column sum without the diagonal, so the first pick is its argmax
+    colsum = S.double().sum(dim=0) - S.diagonal().double()
+    first = int(np.flatnonzero(o == 0)[0])
+    assert colsum[first].item() >= colsum.max().item() * (1 - 1e-12)
+    # f(A) = similarity mass between A and the rest of the class
+    for k in (0, 7):
+        inside = torch.from_numpy(a == k).cuda()
+        members = torch.nonzero(inside).flatten()
+        ref = 0.0
+        for lo in range(0, w.n_c, 5000):
+            rows = S[lo:lo + 5000]
+            outside = (~inside[lo:lo + 5000]).double()
+            ref += (rows[:, members].double().sum(dim=1) * outside).sum().item()
+        assert abs(f[k] - ref) <= 1e-6 * ref, (k, f[k], ref)
+    Sh = S.cpu().numpy()
+    del S
+    steps = [0, 1, 25000, 49000, 49998, 49999]
+    res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps, objective="gc")
+    print(f"  referee {res}", flush=True)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
