@@ -65,6 +65,8 @@ def _load():
     lib.oracle_f_gc.argtypes = [vp, i64, i64, vp, i64]
     lib.oracle_partition_class_gc.restype = i64
     lib.oracle_partition_class_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.oracle_bandwidth.restype = dbl
+    lib.oracle_bandwidth.argtypes = [vp, i32, i64, i64, i64]
     lib.oracle_lockstep_gc.restype = i32
     lib.oracle_lockstep_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, dbl, dbl, vp, vp]
     lib.oracle_partition_dataset.restype = i32
@@ -105,6 +107,16 @@ def similarity(X, sigma2: float, want64: bool = False):
     if rc != 0:
         raise ValueError("oracle_similarity rejected its arguments")
     return (S32, S64) if want64 else S32
+
+
+def bandwidth(X) -> float:
+    """The paper's kernel bandwidth: mean L2 distance over all n^2 ordered pairs of rows of X."""
+    X, dt = _features(X)
+    n, d = X.shape
+    sigma = _load().oracle_bandwidth(_ptr(X), dt, n, d, d)
+    if sigma < 0:
+        raise ValueError("oracle_bandwidth rejected its arguments")
+    return float(sigma)
 
 
 def quota(n_l: int, r) -> np.ndarray:

@@ -820,3 +820,35 @@ int oracle_lockstep_gc(const float *S, int64_t lds, int64_t n, int K, const int6
     free(elem_at); free(state); free(f); free(cnt);
     return rc;
 }
+
+/* ======================================================================================
+ * Bandwidth of the Gaussian kernel (Section 4, "Submodular functions"): the paper sets
+ *   sigma = sum over v, v' in V of ||v - v'||_2  /  n^2,
+ * the mean L2 distance over all n^2 ordered pairs of the set the similarity is built on,
+ * the n pairs of a sample with itself (distance 0) included in the count.
+ * Readings: n = |V| (the formula's n is the size of the set summed over, not the worker
+ * index n of Algorithm 1); the distance is not squared; V is whatever row set the caller
+ * passes (the whole data set, or one class).
+ * Every ordered pair is computed on its own from coordinate differences.
+ * Returns sigma, or -1 on a bad argument; 0 for an empty set.
+ * ====================================================================================== */
+double oracle_bandwidth(const void *X, int dtype, int64_t n, int64_t d, int64_t ldx)
+{
+    if (n < 0 || d < 1 || ldx < d || (n > 0 && !X))
+        return -1.0;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return -1.0;
+    if (n == 0)
+        return 0.0;
+    double total = 0.0;
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double dist2 = 0.0;
+            for (int64_t t = 0; t < d; ++t) {
+                double diff = elem_as_double(X, dtype, i * ldx + t) - elem_as_double(X, dtype, j * ldx + t);
+                dist2 += diff * diff;
+            }
+            total += sqrt(dist2);
+        }
+    return total / ((double)n * (double)n);
+}
