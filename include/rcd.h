@@ -73,6 +73,24 @@ int rcd_similarity(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x
 size_t rcd_similarity_workspace_bytes(int64_t n);
 
 /*
+ * Kernel bandwidth.  Section 4 sets the bandwidth of the Gaussian kernel to the mean
+ * L2 distance over all ordered pairs of the set the similarity is built on:
+ *     sigma = sum_{i,j < n} ||x_i - x_j||_2 / n^2
+ * (the n zero distances of a sample to itself are part of the n^2).  x_i = row i of X,
+ * or row row_index_dev[i] when row_index_dev is non-null, so the set can be the whole
+ * data set or one class.  Distances come from the same Gram tiles as rcd_similarity
+ * (matrix cores, fp32 accumulation, squared distance clamped at 0 before the root);
+ * tile sums and their total are accumulated in double in a fixed order.
+ * *sigma_host receives sigma (0 for n = 0); pass sigma*sigma as sigma2 elsewhere.
+ * Synchronises `stream` before returning.
+ * workspace: rcd_bandwidth_workspace_bytes(n) bytes.
+ */
+int rcd_bandwidth(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x,
+                  const int32_t *row_index_dev, double *sigma_host,
+                  void *workspace_dev, size_t workspace_bytes, void *stream);
+size_t rcd_bandwidth_workspace_bytes(int64_t n);
+
+/*
  * Quota rule.  Algorithm 1, constraint line: C_{l,j} = n_l * r_j / sum_j r_j,
  * made integral by floor; the remainder goes one each to the workers with the
  * largest r (lowest index first among equals), the same workers in every class.

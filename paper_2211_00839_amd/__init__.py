@@ -8,6 +8,7 @@ GPU, calls raise.
 """
 from .binding import (  # noqa: F401
     RcdError,
+    bandwidth,
     class_workspace_bytes,
     dataset_workspace_bytes,
     gain_sweep,

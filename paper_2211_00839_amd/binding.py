@@ -13,7 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "librcd.so")
 _lib = None
 
 EXPORTS = [
-    "rcd_similarity", "rcd_similarity_workspace_bytes", "rcd_quota", "rcd_gain_sweep",
+    "rcd_similarity", "rcd_similarity_workspace_bytes", "rcd_bandwidth", "rcd_bandwidth_workspace_bytes", "rcd_quota", "rcd_gain_sweep",
     "rcd_partition_class", "rcd_partition_dataset", "rcd_partition_class_graph_cut",
     "rcd_partition_dataset_graph_cut", "rcd_class_workspace_bytes",
     "rcd_dataset_workspace_bytes", "rcd_strerror", "rcd_last_hip_error", "rcd_last_stats",
@@ -49,6 +49,10 @@ def load_library():
     lib.rcd_similarity_workspace_bytes.restype = sz
     lib.rcd_similarity_workspace_bytes.argtypes = [i64]
     lib.rcd_quota.restype = i32
+    lib.rcd_bandwidth.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.rcd_bandwidth.restype = i32
+    lib.rcd_bandwidth_workspace_bytes.argtypes = [i64]
+    lib.rcd_bandwidth_workspace_bytes.restype = sz
     lib.rcd_quota.argtypes = [i64, vp, i32, vp]
     lib.rcd_gain_sweep.restype = i32
     lib.rcd_gain_sweep.argtypes = [vp, i64, i64, i32, vp, vp, vp, sz, vp]
@@ -161,6 +165,21 @@ def similarity(X, sigma2: float, row_index=None, out=None, workspace=None):
                               _dev_ptr(out), out.stride(0) if n > 0 else max(n, 1), _dev_ptr(workspace),
                               workspace.numel(), _stream()))
     return out
+
+
+def bandwidth(X, row_index=None, workspace=None) -> float:
+    """The paper's kernel bandwidth sigma: mean L2 distance over all ordered pairs of the rows of X
+    (of the rows row_index selects, if given)."""
+    lib = load_library()
+    n = X.shape[0] if row_index is None else row_index.shape[0]
+    d = X.shape[1]
+    assert X.stride(1) == 1
+    if workspace is None:
+        workspace = _workspace(lib.rcd_bandwidth_workspace_bytes(n), X.device)
+    sigma = np.zeros(1, dtype=np.float64)
+    _check(lib.rcd_bandwidth(_dev_ptr(X), _dtype_code(X), n, d, X.stride(0), _dev_ptr(row_index), _np_ptr(sigma),
+                             _dev_ptr(workspace), workspace.numel(), _stream()))
+    return float(sigma[0])
 
 
 def gain_sweep(S, cur, workspace=None):

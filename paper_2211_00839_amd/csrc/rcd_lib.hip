@@ -220,7 +220,9 @@ int fast_setup()
 {
     if (!g_fast_ready) {
         const void *sim_kernels[] = {reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float>),
-                                     reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16>)};
+                                     reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16>),
+                                     reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float, sim::EPI_DISTANCE>),
+                                     reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16, sim::EPI_DISTANCE>)};
         for (const void *k : sim_kernels)
             HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, sim::pipe::LDS_BYTES));
         const void *rc_kernels[] = {reinterpret_cast<const void *>(&rcd_k_round_rc_fast<float, true>),
@@ -637,24 +639,36 @@ int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, 
         if (dt == RCD_F32)
             hipLaunchKernelGGL(sim::k_gram_rbf_fast<float>, grid, dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream,
                                (const float *)X, (long long)ldx, row_index, (int)n, (int)d, (const float *)sq,
-                               exp_scale, S, (long long)ld_s, ncols_pad);
+                               exp_scale, S, (long long)ld_s, ncols_pad, (double *)nullptr);
         else
             hipLaunchKernelGGL(sim::k_gram_rbf_fast<__bf16>, grid, dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream,
                                (const __bf16 *)X, (long long)ldx, row_index, (int)n, (int)d, (const float *)sq,
-                               exp_scale, S, (long long)ld_s, ncols_pad);
+                               exp_scale, S, (long long)ld_s, ncols_pad, (double *)nullptr);
     } else {
         const dim3 grid((unsigned)((ncols_pad + sim::BN - 1) / sim::BN), (unsigned)((n + sim::BM - 1) / sim::BM));
         if (dt == RCD_F32)
             hipLaunchKernelGGL(sim::k_gram_rbf<float>, grid, dim3(sim::THREADS), 0, stream, (const float *)X,
                                (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
-                               (long long)ld_s, ncols_pad);
+                               (long long)ld_s, ncols_pad, (double *)nullptr);
         else
             hipLaunchKernelGGL(sim::k_gram_rbf<__bf16>, grid, dim3(sim::THREADS), 0, stream, (const __bf16 *)X,
                                (long long)ldx, row_index, (int)n, (int)d, (const float *)sq, exp_scale, S,
-                               (long long)ld_s, ncols_pad);
+                               (long long)ld_s, ncols_pad, (double *)nullptr);
     }
     HIP_TRY(hipGetLastError());
     return RCD_OK;
+}
+
+// Tiles of the pairwise-distance sum: the same Gram kernels with the distance epilogue.
+void bandwidth_tiles(int64_t n, bool fast, int64_t *tiles_m, int64_t *tiles_n)
+{
+    if (fast) {
+        *tiles_m = (n + sim::pipe::TM - 1) / sim::pipe::TM;
+        *tiles_n = (n + sim::pipe::TN - 1) / sim::pipe::TN;
+    } else {
+        *tiles_m = (n + sim::BM - 1) / sim::BM;
+        *tiles_n = (n + sim::BN - 1) / sim::BN;
+    }
 }
 
 int launch_row_norms(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, const int32_t *row_index, float *sq,
@@ -754,6 +768,75 @@ int rcd_similarity(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x
     RCD_TRY(check_workspace(workspace_dev, workspace_bytes, rcd_similarity_workspace_bytes(n)));
     return launch_similarity(X_dev, dt, n, d, ld_x, row_index_dev, sigma2, S_dev, ld_s, (int)n,
                              (float *)workspace_dev, (hipStream_t)stream);
+}
+
+size_t rcd_bandwidth_workspace_bytes(int64_t n)
+{
+    if (n <= 0) return 0;
+    // row norms, one double per tile (whichever path's tile list is longer), the total
+    int64_t tm, tn, fm, fn;
+    bandwidth_tiles(n, false, &tm, &tn);
+    bandwidth_tiles(n, true, &fm, &fn);
+    const int64_t slots = std::max(tm * tn, ((fm + 1) / 2) * (fm + 1));
+    return up256((size_t)n * 4) + up256((size_t)slots * 8) + 256;
+}
+
+int rcd_bandwidth(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x, const int32_t *row_index_dev,
+                  double *sigma_host, void *workspace_dev, size_t workspace_bytes, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
+    if (n < 0 || d < 1 || ld_x < d || !sigma_host) return RCD_ERR_INVALID_ARG;
+    if (n > (int64_t)0x7fffff00 || d > (int64_t)0x7fffff00) return RCD_ERR_UNSUPPORTED;
+    *sigma_host = 0.0;
+    if (n == 0) return RCD_OK;
+    if (!X_dev) return RCD_ERR_INVALID_ARG;
+    RCD_TRY(check_workspace(workspace_dev, workspace_bytes, rcd_bandwidth_workspace_bytes(n)));
+    Carver cv(workspace_dev, workspace_bytes);
+    float *sq = cv.take<float>((size_t)n);
+    const bool fast = rows_fit_fast_path(X_dev, dt, d, ld_x);
+    int64_t tm, tn;
+    bandwidth_tiles(n, fast, &tm, &tn);
+    if (fast) {
+        // the fast kernel walks the tiles on and above the diagonal, folded into a rectangle
+        tn = tm + 1;
+        tm = (tm + 1) / 2;
+    }
+    double *pair_sums = cv.take<double>((size_t)(tm * tn));
+    double *total = cv.take<double>(1);
+    if (cv.fail) return RCD_ERR_WORKSPACE;
+    RCD_TRY(launch_row_norms(X_dev, dt, n, d, ld_x, row_index_dev, sq, stream));
+    if (fast) {
+        RCD_TRY(fast_setup());
+        const dim3 grid((unsigned)((tm * tn + 7) / 8 * 8));
+        if (dt == RCD_F32)
+            hipLaunchKernelGGL((sim::k_gram_rbf_fast<float, sim::EPI_DISTANCE>), grid, dim3(sim::THREADS),
+                               sim::pipe::LDS_BYTES, stream, (const float *)X_dev, (long long)ld_x, row_index_dev, (int)n,
+                               (int)d, (const float *)sq, 1.f, (float *)nullptr, 0LL, (int)n, pair_sums);
+        else
+            hipLaunchKernelGGL((sim::k_gram_rbf_fast<__bf16, sim::EPI_DISTANCE>), grid, dim3(sim::THREADS),
+                               sim::pipe::LDS_BYTES, stream, (const __bf16 *)X_dev, (long long)ld_x, row_index_dev, (int)n,
+                               (int)d, (const float *)sq, 1.f, (float *)nullptr, 0LL, (int)n, pair_sums);
+    } else {
+        const dim3 grid((unsigned)tn, (unsigned)tm);
+        if (dt == RCD_F32)
+            hipLaunchKernelGGL((sim::k_gram_rbf<float, sim::EPI_DISTANCE>), grid, dim3(sim::THREADS), 0, stream,
+                               (const float *)X_dev, (long long)ld_x, row_index_dev, (int)n, (int)d, (const float *)sq,
+                               1.f, (float *)nullptr, 0LL, (int)n, pair_sums);
+        else
+            hipLaunchKernelGGL((sim::k_gram_rbf<__bf16, sim::EPI_DISTANCE>), grid, dim3(sim::THREADS), 0, stream,
+                               (const __bf16 *)X_dev, (long long)ld_x, row_index_dev, (int)n, (int)d, (const float *)sq,
+                               1.f, (float *)nullptr, 0LL, (int)n, pair_sums);
+    }
+    hipLaunchKernelGGL(sim::k_sum_doubles, dim3(1), dim3(1024), 0, stream, (const double *)pair_sums,
+                       (long long)(tm * tn), total);
+    HIP_TRY(hipGetLastError());
+    double pairs = 0.0;
+    HIP_TRY(hipMemcpyAsync(&pairs, total, sizeof pairs, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    // every unordered pair was summed once; the n zero distances of a sample to itself add nothing
+    *sigma_host = 2.0 * pairs / ((double)n * (double)n);
+    return RCD_OK;
 }
 
 int rcd_quota(int64_t n_l, const int32_t *r_host, int K, int64_t *cap_host)

@@ -40,6 +40,25 @@ __device__ __forceinline__ float rbf_value(float gram, float sqi_s, float sqj_s,
     return __builtin_amdgcn_fmed3f(fast_exp2(fmaf(gram, scale2, sqi_s + sqj_s)), 0.f, 1.f);
 }
 
+enum { EPI_RBF = 0, EPI_DISTANCE = 1 };
+
+// The L2 distance from the Gram value and the two squared norms, clamped at 0 before the root.
+__device__ __forceinline__ float distance_value(float gram, float sqi, float sqj)
+{
+    return __builtin_sqrtf(fmaxf(fmaf(gram, -2.f, sqi + sqj), 0.f));
+}
+
+// Sum of one tile's distances over its 256 threads in a fixed order (lanes by butterfly, then the
+// four waves in order); thread 0 stores it.  `scratch`: 4 doubles of LDS nobody else is using.
+__device__ __forceinline__ void tile_distance_sum(double mine, double *scratch, int tid, double *out)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
+    if ((tid & 63) == 0) scratch[tid >> 6] = mine;
+    __syncthreads();
+    if (tid == 0) *out = ((scratch[0] + scratch[1]) + scratch[2]) + scratch[3];
+}
+
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
 
@@ -457,11 +476,15 @@ __device__ __forceinline__ bool tile_of_workgroup(int w, int nwg, int tiles_m, i
 
 // Gram tile + Gaussian epilogue, fast path.  grid = tiles rounded up to a multiple of 8,
 // dynamic LDS = pipe::LDS_BYTES.  Columns n .. ncols_pad-1 of the output are written as 0.
-template <typename T>
+// EPI = EPI_DISTANCE: nothing is stored; the sum of the tile's distances over its pairs i < j goes to
+// one slot of pair_sums; call with exp_scale = 1, ncols_pad = n and a grid of
+// ((tiles + 1) / 2) * (tiles + 1) workgroups rounded up to a multiple of 8, tiles = ceil(n / 256),
+// which is also the number of slots.
+template <typename T, int EPI = EPI_RBF>
 __global__ void __launch_bounds__(THREADS, 1)
 k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
                 const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
-                int ncols_pad)
+                int ncols_pad, double *__restrict__ pair_sums)
 {
     using namespace pipe;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -470,10 +493,34 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
     const int wr = wave >> 1, wc = wave & 1;
     const int tiles_m = (n + TM - 1) / TM, tiles_n = (ncols_pad + TN - 1) / TN;
     int ti, tj;
-    if (!tile_of_workgroup((int)blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, &ti, &tj)) return;
+    size_t sum_slot = 0;
+    if constexpr (EPI == EPI_DISTANCE) {
+        // Only tiles on or above the diagonal carry pairs (i < j).  Tile row r (tiles_m - r of them) and
+        // tile row tiles_m - 1 - r (r + 1 of them) together fill one row of a (tiles_m + 1)-wide
+        // rectangle with (tiles_m + 1) / 2 rows, which is dealt to the workgroups like any tile grid.
+        int r, c;
+        if (!tile_of_workgroup((int)blockIdx.x, (int)gridDim.x, (tiles_m + 1) / 2, tiles_m + 1, &r, &c)) return;
+        sum_slot = (size_t)r * (tiles_m + 1) + c;
+        if (c < tiles_m - r) {
+            ti = r;
+            tj = r + c;
+        } else {
+            ti = tiles_m - 1 - r;
+            tj = ti + (c - (tiles_m - r));
+            if (ti == r) {
+                // odd tile count: the middle tile row has no partner, its slots past the row's end stay empty
+                if (tid == 0) pair_sums[sum_slot] = 0.0;
+                return;
+            }
+        }
+    } else {
+        if (!tile_of_workgroup((int)blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, &ti, &tj)) return;
+    }
     const int i0 = ti * TM, j0 = tj * TN;
 
-    if (j0 >= n) {
+    if constexpr (EPI == EPI_DISTANCE) {
+        // every tile of the list holds work
+    } else if (j0 >= n) {
         // tile entirely in the zero padding of the output pitch
         for (int e = tid; e < TM * TN; e += THREADS) {
             const int i = i0 + e / TN, j = j0 + e % TN;
@@ -513,6 +560,39 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
     __syncthreads();
     const float scale2 = -2.f * exp_scale;
     const int r0 = i0 + wr * 128 + (lane >> 5) * 4;
+    if constexpr (EPI == EPI_DISTANCE) {
+        double total = 0.0;
+        auto sum_up = [&](auto plain_tag) {
+            constexpr bool PLAIN = decltype(plain_tag)::value;   // interior tile above the diagonal: every pair counts
+            int i = r0;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int rl = wr * 128 + a * 32 + rq * 8 + (lane >> 5) * 4;
+                    const float4 sqi4 = *reinterpret_cast<const float4 *>(sq_rows + rl);
+                    const float sqi[4] = {sqi4.x, sqi4.y, sqi4.z, sqi4.w};
+                    float part = 0.f;      // 16 distances at a time in fp32, then into the double
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            float dist = distance_value(acc_read(acc[a][b][rq * 4 + e]), sqi[e], sqj[b]);
+                            if constexpr (!PLAIN) dist = (jj[b] > i && jj[b] < n) ? dist : 0.f;
+                            part += dist;
+                        }
+                        i += (e == 3) ? 5 : 1;
+                    }
+                    total += (double)part;
+                    pin_schedule();
+                }
+            }
+        };
+        if (i0 + TM <= n && j0 + TN <= n && tj > ti) sum_up(std::true_type{});
+        else sum_up(std::false_type{});
+        tile_distance_sum(total, reinterpret_cast<double *>(lds + 2048), tid, &pair_sums[sum_slot]);
+        return;
+    }
     float *dst0 = S + (size_t)r0 * lds_out + (j0 + wc * 128 + (lane & 31));
     // one running row pointer per lane: rows advance +1 +1 +1 +5 through the accumulator layout
     const long long step1 = lds_out, step5 = 5 * lds_out;
@@ -551,11 +631,13 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
 }
 
 // Gram tile + Gaussian epilogue, general path (any alignment, any d).  grid = (column tiles, row tiles).
-template <typename T>
+// EPI = EPI_DISTANCE: the tile's distance sum goes to pair_sums[blockIdx.y * gridDim.x + blockIdx.x]
+// (exp_scale = 1, ncols_pad = n).
+template <typename T, int EPI = EPI_RBF>
 __global__ void __launch_bounds__(THREADS, 2)
 k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
            const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
-           int ncols_pad)
+           int ncols_pad, double *__restrict__ pair_sums)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
 
@@ -564,7 +646,13 @@ k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ r
     const int wr = wave >> 1, wc = wave & 1;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BN;
 
-    if (j0 >= n) {
+    if constexpr (EPI == EPI_DISTANCE) {
+        if (j0 + BN <= i0 + 1) {
+            // no column of this tile lies right of the diagonal: its pairs are counted from the other side
+            if (tid == 0) pair_sums[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = 0.0;
+            return;
+        }
+    } else if (j0 >= n) {
         // tile entirely in the zero padding of the output pitch
         for (int e = tid; e < BM * BN; e += THREADS) {
             const int i = i0 + e / BN, j = j0 + e % BN;
@@ -601,6 +689,33 @@ k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ r
     const float scale2 = -2.f * exp_scale;
     const bool interior = i0 + BM <= n && j0 + BN <= n;
     const bool on_diagonal = i0 < j0 + BN && j0 < i0 + BM;
+    if constexpr (EPI == EPI_DISTANCE) {
+        double total = 0.0;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int j = j0 + wc * 64 + b * 32 + (lane & 31);
+            const float sqj = j < n ? sq[j] : 0.f;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int rl = wr * 128 + a * 32 + rq * 8 + (lane >> 5) * 4;
+                    const float4 sqi4 = *reinterpret_cast<const float4 *>(sq_rows + rl);
+                    const float sqi[4] = {sqi4.x, sqi4.y, sqi4.z, sqi4.w};
+                    float part = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float dist = distance_value(acc[a][b][rq * 4 + e], sqi[e], sqj);
+                        part += (j > i0 + rl + e && j < n) ? dist : 0.f;
+                    }
+                    total += (double)part;
+                }
+            }
+        }
+        tile_distance_sum(total, reinterpret_cast<double *>(lds + 2048), tid,
+                          &pair_sums[(size_t)blockIdx.y * gridDim.x + blockIdx.x]);
+        return;
+    }
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int j = j0 + wc * 64 + b * 32 + (lane & 31);
@@ -627,6 +742,22 @@ k_gram_rbf(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ r
             }
         }
     }
+}
+
+// out[0] = sum of count doubles, in a fixed order: one workgroup, strided partial sums, then a tree.
+__global__ void __launch_bounds__(1024)
+k_sum_doubles(const double *__restrict__ v, long long count, double *__restrict__ out)
+{
+    __shared__ double part[1024];
+    double a = 0.0;
+    for (long long i = threadIdx.x; i < count; i += 1024) a += v[i];
+    part[threadIdx.x] = a;
+    __syncthreads();
+    for (int w = 512; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = part[0];
 }
 
 } // namespace sim
