@@ -65,6 +65,10 @@ def _load():
     lib.oracle_f_gc.argtypes = [vp, i64, i64, vp, i64]
     lib.oracle_partition_class_gc.restype = i64
     lib.oracle_partition_class_gc.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.oracle_worker_shards.restype = i32
+    lib.oracle_worker_shards.argtypes = [vp, i64, i32, vp, vp]
+    lib.oracle_batch_sizes.restype = i32
+    lib.oracle_batch_sizes.argtypes = [i64, vp, i32, vp]
     lib.oracle_bandwidth.restype = dbl
     lib.oracle_bandwidth.argtypes = [vp, i32, i64, i64, i64]
     lib.oracle_lockstep_gc.restype = i32
@@ -107,6 +111,26 @@ def similarity(X, sigma2: float, want64: bool = False):
     if rc != 0:
         raise ValueError("oracle_similarity rejected its arguments")
     return (S32, S64) if want64 else S32
+
+
+def worker_shards(assign, K: int):
+    """Per-worker ascending index lists of an assignment (-1 = in no list).  Returns (index[:total], offset[K+1])."""
+    assign = np.ascontiguousarray(assign, dtype=np.int32)
+    N = len(assign)
+    index = np.full(max(N, 1), -1, dtype=np.int32)
+    offset = np.zeros(K + 1, dtype=np.int64)
+    if _load().oracle_worker_shards(_ptr(assign), N, int(K), _ptr(index), _ptr(offset)) != 0:
+        raise ValueError("oracle_worker_shards rejected its arguments")
+    return index[: offset[K]], offset
+
+
+def batch_sizes(B: int, r) -> np.ndarray:
+    """Batch size per worker: B r_i / r_1 to the nearest integer, at least 1."""
+    r = np.ascontiguousarray(r, dtype=np.int64)
+    out = np.zeros(len(r), dtype=np.int64)
+    if _load().oracle_batch_sizes(int(B), _ptr(r), len(r), _ptr(out)) != 0:
+        raise ValueError("oracle_batch_sizes rejected its arguments")
+    return out
 
 
 def bandwidth(X) -> float:

@@ -852,3 +852,50 @@ double oracle_bandwidth(const void *X, int dtype, int64_t n, int64_t d, int64_t 
         }
     return total / ((double)n * (double)n);
 }
+
+/* ======================================================================================
+ * Hand-off to Algorithm 2 (its initialisation line: worker i imports its subset A_i, and
+ * runs with a batch size set from the capacity ratios).
+ * ====================================================================================== */
+
+/* Worker k's list = the samples with assign == k in ascending order; the lists are laid
+ * end to end in index[], offset[k] .. offset[k+1] delimiting list k (offset has K+1 entries).
+ * Samples with assign == -1 belong to no list.  Returns 0, or -1 on a bad argument or an
+ * assignment outside [-1, K). */
+int oracle_worker_shards(const int32_t *assign, int64_t N, int K, int32_t *index, int64_t *offset)
+{
+    if (N < 0 || K < 1 || !offset || (N > 0 && (!assign || !index)))
+        return -1;
+    for (int64_t i = 0; i < N; ++i)
+        if (assign[i] < -1 || assign[i] >= K)
+            return -1;
+    int64_t at = 0;
+    for (int k = 0; k < K; ++k) {
+        offset[k] = at;
+        for (int64_t i = 0; i < N; ++i)
+            if (assign[i] == k)
+                index[at++] = (int32_t)i;
+    }
+    offset[K] = at;
+    return 0;
+}
+
+/* Batch sizes.  The text after Algorithm 2 says a worker's batch size, like its shard, is
+ * proportional to its processing speed, so that all workers finish their local iterations in
+ * the same time; the algorithm box prints the factor as r_1 / r_i, which would do the
+ * opposite.  Reading taken: batch_i = B r_i / r_1 (worker 1 runs B), to the nearest integer
+ * with halves rounded up, and never less than 1. */
+int oracle_batch_sizes(int64_t B, const int64_t *r, int K, int64_t *batch)
+{
+    if (B < 1 || K < 1 || !r || !batch)
+        return -1;
+    for (int k = 0; k < K; ++k)
+        if (r[k] < 1)
+            return -1;
+    for (int k = 0; k < K; ++k) {
+        double exact = (double)B * (double)r[k] / (double)r[0];
+        int64_t q = (int64_t)floor(exact + 0.5);
+        batch[k] = q < 1 ? 1 : q;
+    }
+    return 0;
+}
