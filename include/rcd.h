@@ -173,6 +173,28 @@ int rcd_partition_dataset_graph_cut(const void *X_dev, int dt, int64_t N, int64_
                                     int32_t *assign_dev, int32_t *order_dev, double *obj_host,
                                     void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/*
+ * Hand-off to the training loop (Algorithm 2, initialisation: worker i imports its subset A_i
+ * of the partition and runs with a batch size scaled by the capacity ratios).
+ *
+ * rcd_worker_shards: per-worker index lists from an assignment (stable counting sort by worker).
+ *   assign_dev[N] in [0, K), or -1 for a sample given to nobody (skipped)
+ *   index_dev[N]  receives the sample indices grouped by worker, ascending inside a worker:
+ *                 worker k owns index_dev[offset_host[k] .. offset_host[k+1])
+ *   offset_host[K+1]  offset_host[K] = number of assigned samples
+ * A value outside [-1, K) gives RCD_ERR_BAD_LABEL.  Synchronises `stream` before returning.
+ *
+ * rcd_batch_sizes (host only): batch_host[k] = B * r_k / r_1 to the nearest integer (halves up,
+ * at least 1), so that worker 1 runs batch B and every worker's batch is proportional to its
+ * capacity.  The algorithm box prints the factor the other way round (r_1 / r_i); the text
+ * says batch and shard are proportional to the processing speed and that all workers then
+ * finish a round in the same time, which only this direction gives.
+ */
+int rcd_worker_shards(const int32_t *assign_dev, int64_t N, int K, int32_t *index_dev, int64_t *offset_host,
+                      void *workspace_dev, size_t workspace_bytes, void *stream);
+size_t rcd_worker_shards_workspace_bytes(int64_t N, int K);
+int rcd_batch_sizes(int64_t B, const int32_t *r_host, int K, int64_t *batch_host);
+
 /* Workspace sizes in bytes (multiples of 256; the pointer must be 256-byte aligned).
  * rcd_class_workspace_bytes: what rcd_partition_class / rcd_gain_sweep need for a
  *   class of n samples (stored mode includes a private n x ld copy of S).

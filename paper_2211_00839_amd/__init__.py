@@ -9,6 +9,7 @@ GPU, calls raise.
 from .binding import (  # noqa: F401
     RcdError,
     bandwidth,
+    batch_sizes,
     class_workspace_bytes,
     dataset_workspace_bytes,
     gain_sweep,
@@ -23,6 +24,7 @@ from .binding import (  # noqa: F401
     quota,
     similarity,
     strerror,
+    worker_shards,
 )
 
 F32 = 0

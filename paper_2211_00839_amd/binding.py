@@ -13,7 +13,8 @@ _LIB_PATH = os.path.join(_HERE, "librcd.so")
 _lib = None
 
 EXPORTS = [
-    "rcd_similarity", "rcd_similarity_workspace_bytes", "rcd_bandwidth", "rcd_bandwidth_workspace_bytes", "rcd_quota", "rcd_gain_sweep",
+    "rcd_similarity", "rcd_similarity_workspace_bytes", "rcd_bandwidth", "rcd_bandwidth_workspace_bytes", "rcd_quota",
+    "rcd_worker_shards", "rcd_worker_shards_workspace_bytes", "rcd_batch_sizes", "rcd_gain_sweep",
     "rcd_partition_class", "rcd_partition_dataset", "rcd_partition_class_graph_cut",
     "rcd_partition_dataset_graph_cut", "rcd_class_workspace_bytes",
     "rcd_dataset_workspace_bytes", "rcd_strerror", "rcd_last_hip_error", "rcd_last_stats",
@@ -53,6 +54,12 @@ def load_library():
     lib.rcd_bandwidth.restype = i32
     lib.rcd_bandwidth_workspace_bytes.argtypes = [i64]
     lib.rcd_bandwidth_workspace_bytes.restype = sz
+    lib.rcd_worker_shards.argtypes = [vp, i64, i32, vp, vp, vp, sz, vp]
+    lib.rcd_worker_shards.restype = i32
+    lib.rcd_worker_shards_workspace_bytes.argtypes = [i64, i32]
+    lib.rcd_worker_shards_workspace_bytes.restype = sz
+    lib.rcd_batch_sizes.argtypes = [i64, vp, i32, vp]
+    lib.rcd_batch_sizes.restype = i32
     lib.rcd_quota.argtypes = [i64, vp, i32, vp]
     lib.rcd_gain_sweep.restype = i32
     lib.rcd_gain_sweep.argtypes = [vp, i64, i64, i32, vp, vp, vp, sz, vp]
@@ -134,6 +141,30 @@ def quota(n_l: int, r) -> np.ndarray:
     cap = np.zeros(len(r), dtype=np.int64)
     _check(load_library().rcd_quota(int(n_l), _np_ptr(r), len(r), _np_ptr(cap)))
     return cap
+
+
+def worker_shards(assign, K: int, workspace=None):
+    """Per-worker index lists of an assignment.  Returns (index int32[N] device, offset int64[K+1] numpy):
+    worker k owns index[offset[k]:offset[k+1]], ascending; samples with assign == -1 are in no list."""
+    import torch
+
+    lib = load_library()
+    N = assign.shape[0]
+    assert assign.dtype == torch.int32 and assign.is_contiguous()
+    index = torch.empty(N, dtype=torch.int32, device=assign.device)
+    offset = np.zeros(K + 1, dtype=np.int64)
+    if workspace is None:
+        workspace = _workspace(lib.rcd_worker_shards_workspace_bytes(N, K), assign.device)
+    _check(lib.rcd_worker_shards(_dev_ptr(assign), N, int(K), _dev_ptr(index), _np_ptr(offset), _dev_ptr(workspace),
+                                 workspace.numel(), _stream()))
+    return index, offset
+
+
+def batch_sizes(B: int, r) -> np.ndarray:
+    r = np.ascontiguousarray(r, dtype=np.int32)
+    out = np.zeros(len(r), dtype=np.int64)
+    _check(load_library().rcd_batch_sizes(int(B), _np_ptr(r), len(r), _np_ptr(out)))
+    return out
 
 
 def class_workspace_bytes(n: int, K: int, mode: int = 1) -> int:

@@ -862,6 +862,71 @@ int rcd_quota(int64_t n_l, const int32_t *r_host, int K, int64_t *cap_host)
     return RCD_OK;
 }
 
+size_t rcd_worker_shards_workspace_bytes(int64_t N, int K)
+{
+    if (N <= 0 || K < 1) return 0;
+    const size_t nchunks = (size_t)((N + split::CHUNK - 1) / split::CHUNK);
+    return up256(nchunks * K * 4) + 2 * up256((size_t)K * 4) + up256(sizeof(RcdPlan));
+}
+
+int rcd_worker_shards(const int32_t *assign_dev, int64_t N, int K, int32_t *index_dev, int64_t *offset_host,
+                      void *workspace_dev, size_t workspace_bytes, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    RCD_TRY(check_common(N, K));
+    if (!offset_host) return RCD_ERR_INVALID_ARG;
+    for (int k = 0; k <= K; ++k) offset_host[k] = 0;
+    if (N == 0) return RCD_OK;
+    if (!assign_dev || !index_dev) return RCD_ERR_INVALID_ARG;
+    RCD_TRY(check_workspace(workspace_dev, workspace_bytes, rcd_worker_shards_workspace_bytes(N, K)));
+    // the class split's stable counting sort, keyed by worker instead of label
+    const int nchunks = (int)((N + split::CHUNK - 1) / split::CHUNK);
+    Carver cv(workspace_dev, workspace_bytes);
+    int32_t *chunk_hist = cv.take<int32_t>((size_t)nchunks * K);
+    int32_t *count_dev = cv.take<int32_t>((size_t)K);
+    int32_t *offset_dev = cv.take<int32_t>((size_t)K);
+    RcdPlan *flag = reinterpret_cast<RcdPlan *>(cv.take<char>(sizeof(RcdPlan)));
+    if (cv.fail) return RCD_ERR_WORKSPACE;
+    HIP_TRY(hipMemsetAsync(flag, 0, sizeof(RcdPlan), stream));
+    hipLaunchKernelGGL(split::k_hist, dim3(nchunks), dim3(64), (size_t)K * 4, stream, assign_dev, (long long)N, K,
+                       chunk_hist, flag, 1);
+    hipLaunchKernelGGL(split::k_scan, dim3((K + 255) / 256), dim3(256), 0, stream, chunk_hist, nchunks, K, count_dev);
+    HIP_TRY(hipGetLastError());
+    std::vector<int32_t> count(K), offset(K);
+    RcdPlan flag_host;
+    HIP_TRY(hipMemcpyAsync(count.data(), count_dev, sizeof(int32_t) * K, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipMemcpyAsync(&flag_host, flag, sizeof flag_host, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (flag_host.bad) return RCD_ERR_BAD_LABEL;
+    int32_t run = 0;
+    for (int k = 0; k < K; ++k) {
+        offset[k] = run;
+        offset_host[k] = run;
+        run += count[k];
+    }
+    offset_host[K] = run;
+    HIP_TRY(hipMemcpyAsync(offset_dev, offset.data(), sizeof(int32_t) * K, hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(split::k_scatter, dim3(nchunks), dim3(64), (size_t)K * 4, stream, assign_dev, (long long)N, K,
+                       (const int32_t *)chunk_hist, (const int32_t *)offset_dev, index_dev);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    return RCD_OK;
+}
+
+int rcd_batch_sizes(int64_t B, const int32_t *r_host, int K, int64_t *batch_host)
+{
+    if (B < 1 || K < 1 || !r_host || !batch_host) return RCD_ERR_INVALID_ARG;
+    for (int k = 0; k < K; ++k)
+        if (r_host[k] < 1) return RCD_ERR_BAD_CAPACITY;
+    for (int k = 0; k < K; ++k) {
+        // B r_k / r_1 to the nearest integer (halves up), never below 1
+        const __int128 num = (__int128)B * r_host[k] * 2 + r_host[0];
+        const int64_t q = (int64_t)(num / ((__int128)2 * r_host[0]));
+        batch_host[k] = q < 1 ? 1 : q;
+    }
+    return RCD_OK;
+}
+
 size_t rcd_class_workspace_bytes(int64_t n, int K, int mode)
 {
     if (n <= 0 || K < 1 || K > RCD_MAX_K) return 0;
@@ -1046,7 +1111,7 @@ static int partition_dataset_impl(int objective, const void *X_dev, int dt, int6
     if (cv.fail) return RCD_ERR_WORKSPACE;
     HIP_TRY(hipMemsetAsync(flag, 0, sizeof(RcdPlan), stream));
     hipLaunchKernelGGL(split::k_hist, dim3(nchunks), dim3(64), (size_t)L * 4, stream, labels_dev, (long long)N, L,
-                       chunk_hist, flag);
+                       chunk_hist, flag, 0);
     hipLaunchKernelGGL(split::k_scan, dim3((L + 255) / 256), dim3(256), 0, stream, chunk_hist, nchunks, L,
                        class_count);
     HIP_TRY(hipGetLastError());

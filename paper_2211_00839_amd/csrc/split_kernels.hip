@@ -10,8 +10,11 @@ namespace split {
 constexpr int CHUNK = 1024;   // samples per chunk, one wave per chunk
 
 // chunk_hist[chunk][l] = number of samples with label l in the chunk; flags bad labels.
+// allow_unassigned: a label of -1 is not an error, the sample just belongs nowhere (worker shards of a
+// partition that left samples over).
 __global__ void __launch_bounds__(64)
-k_hist(const int32_t *__restrict__ labels, long long N, int L, int32_t *__restrict__ chunk_hist, RcdPlan *plan)
+k_hist(const int32_t *__restrict__ labels, long long N, int L, int32_t *__restrict__ chunk_hist, RcdPlan *plan,
+       int allow_unassigned = 0)
 {
     extern __shared__ int s_cnt[];
     const int lane = threadIdx.x;
@@ -23,8 +26,8 @@ k_hist(const int32_t *__restrict__ labels, long long N, int L, int32_t *__restri
         const long long i = base + g * 64 + lane;
         if (i < N) {
             const int lab = labels[i];
-            if (lab < 0 || lab >= L) bad = 1;
-            else atomicAdd(&s_cnt[lab], 1);
+            if (lab >= 0 && lab < L) atomicAdd(&s_cnt[lab], 1);
+            else if (!(allow_unassigned && lab == -1)) bad = 1;
         }
     }
     __syncthreads();

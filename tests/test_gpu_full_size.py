@@ -342,3 +342,42 @@ def test_large_class_one_full_class_graph_cut(rcd):
     res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps, objective="gc")
     print(f"  referee {res}", flush=True)
     assert res["rc"] == 0 and res["checked"] == len(steps), res
+
+
+def test_whole_data_set_greedmax_incremental(rcd):
+    # the cifar10 workload's 50 000 samples as ONE class (no class split: the whole-set greedy the paper's
+    # class-wise scheme is compared with), K = 4, similarity stored (10 GB), all 50 000 steps by the
+    # incremental route; invariants, objectives from the definition, sampled steps refereed on the same S
+    print("whole-set GreedMax: cifar10 features as one class of 50 000", flush=True)
+    ds = si.make_dataset(si.WORKLOADS["cifar10"])
+    N = ds.X.shape[0]
+    K = len(ds.r)
+    labels = torch.zeros(N, dtype=torch.int32, device="cuda")
+    Xd = dev(ds.X)
+    _, full = rcd.dataset_workspace_bytes(N, 1, N, K, rcd.MODE_INCREMENTAL)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    a, o, f = rcd.partition_dataset(Xd, labels, 1, ds.r, ds.sigma2, rcd.MODE_INCREMENTAL, ws)
+    stats = rcd.last_stats()
+    print(f"  stats {stats}", flush=True)
+    del ws
+    a, o = a.cpu().numpy(), o.cpu().numpy()
+    cap = oracle.quota(N, ds.r)
+    assert stats["steps"] == N
+    assert np.bincount(a, minlength=K).tolist() == cap.tolist()
+    assert np.array_equal(np.sort(o), np.arange(N))
+    S = rcd.similarity(Xd, ds.sigma2)
+    for k in range(K):
+        members = torch.from_numpy(np.flatnonzero(a == k)).cuda()
+        ref = 0.0
+        for lo in range(0, N, 5000):
+            ref += S[lo:lo + 5000][:, members].max(dim=1).values.double().sum().item()
+        assert abs(f[0, k] - ref) <= 1e-4 * ref
+    Sh = S.cpu().numpy()
+    del S
+    steps = [0, 1, 3, 4, 5, 1000, 25000, 49998, 49999]
+    res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps)
+    print(f"  referee {res}", flush=True)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
+    # without the class split nothing balances the labels: the shards' class counts are no longer the quotas
+    per = np.stack([np.bincount(ds.labels[a == k], minlength=ds.L) for k in range(K)])
+    print(f"  class counts per worker without the class split:\n{per}", flush=True)
