@@ -44,7 +44,8 @@ typedef enum {
 typedef enum { RCD_F32 = 0, RCD_BF16 = 1 } rcd_dtype;
 
 typedef enum {
-    RCD_MODE_AUTO = 0,     /* stored if the workspace can hold at least one class's S, else recompute */
+    RCD_MODE_AUTO = 0,     /* RCD_MODE_INCREMENTAL if the workspace can hold at least one class's S, else
+                              RCD_MODE_RECOMPUTE */
     RCD_MODE_STORED = 1,   /* build S per class once, stream it in every gain sweep */
     RCD_MODE_RECOMPUTE = 2, /* never store S: rebuild its tiles from X inside every gain sweep */
     RCD_MODE_INCREMENTAL = 3 /* stored S, and every block's gains are kept current from step to step:

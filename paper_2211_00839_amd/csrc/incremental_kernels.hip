@@ -140,17 +140,41 @@ namespace {
 
 struct IncShared {
     RcdClass d;
-    double wbest[RCD_STEP_THREADS / 64];
+    unsigned long long wkey[RCD_STEP_THREADS / 64];
     int wv[RCD_STEP_THREADS / 64];
     int wcount[RCD_STEP_THREADS / 64];
     int sj[INC_SMALL];
     float sold[INC_SMALL], snew[INC_SMALL];
 };
 
-// better of two (gain, sample) pairs: larger gain, then the smaller sample index
-__device__ __forceinline__ void inc_better(double &g, int &v, double og, int ov)
+// Order-preserving 64-bit key of a double (no NaNs here; -0 is made +0 first so that equal values
+// get equal keys), and back.
+__device__ __forceinline__ unsigned long long inc_key(double x)
 {
-    if (og > g || (og == g && ov < v)) { g = og; v = ov; }
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x + 0.0);
+    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double inc_value(unsigned long long k)
+{
+    return __longlong_as_double((long long)((k >> 63) ? (k & 0x7fffffffffffffffull) : ~k));
+}
+
+// better of two (key, sample) pairs: larger key, then the smaller sample index
+__device__ __forceinline__ void inc_better(unsigned long long &k, int &v, unsigned long long ok, int ov)
+{
+    if (ok > k || (ok == k && ov < v)) { k = ok; v = ov; }
+}
+
+// The same over the wave, result in every lane: three maximum reductions on 32-bit halves (value high
+// word, low word among those, complemented sample index among those), no trips through LDS.
+__device__ __forceinline__ void inc_wave_best(unsigned long long &key, int &v)
+{
+    const unsigned hi = (unsigned)(key >> 32), lo = (unsigned)key;
+    const unsigned mhi = wave_max_u32(hi);
+    const unsigned mlo = wave_max_u32(hi == mhi ? lo : 0u);
+    const unsigned mv = wave_max_u32(hi == mhi && lo == mlo ? ~(unsigned)v : 0u);
+    key = ((unsigned long long)mhi << 32) | mlo;
+    v = (int)~mv;
 }
 
 } // namespace
@@ -219,18 +243,15 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
             const double x = g[v];
             if (x > best) { best = x; bv = v; }      // ascending v per thread: the first maximum stays
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const double og = __shfl_xor(best, off);
-            const int ov = __shfl_xor(bv, off);
-            inc_better(best, bv, og, ov);
-        }
-        if (lane == 0) { sh.wbest[wave] = best; sh.wv[wave] = bv; }
+        unsigned long long key = inc_key(best);
+        inc_wave_best(key, bv);
+        if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
         __syncthreads();
-        best = sh.wbest[0];
+        key = sh.wkey[0];
         bv = sh.wv[0];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) inc_better(best, bv, sh.wbest[w], sh.wv[w]);
+        for (int w = 1; w < NW; ++w) inc_better(key, bv, sh.wkey[w], sh.wv[w]);
+        best = inc_value(key);
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }          // no candidate left (cannot happen while t < total <= n)
 
@@ -437,18 +458,15 @@ rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
             const double x = g[v];
             if (x > best) { best = x; bv = v; }
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const double og = __shfl_xor(best, off);
-            const int ov = __shfl_xor(bv, off);
-            inc_better(best, bv, og, ov);
-        }
-        if (lane == 0) { sh.wbest[wave] = best; sh.wv[wave] = bv; }
+        unsigned long long key = inc_key(best);
+        inc_wave_best(key, bv);
+        if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
         __syncthreads();
-        best = sh.wbest[0];
+        key = sh.wkey[0];
         bv = sh.wv[0];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) inc_better(best, bv, sh.wbest[w], sh.wv[w]);
+        for (int w = 1; w < NW; ++w) inc_better(key, bv, sh.wkey[w], sh.wv[w]);
+        best = inc_value(key);
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }
         __syncthreads();           // everyone has read wbest / wv and the block state of this step

@@ -1146,6 +1146,8 @@ static int partition_dataset_impl(int objective, const void *X_dev, int dt, int6
                                 up256((size_t)max_count * 4);
         stored = need_one <= workspace_bytes && stored_supported(max_count, K);
     }
+    // left to choose, the library keeps the gains current instead of sweeping: same decisions, far fewer bytes
+    const bool auto_incremental = mode == RCD_MODE_AUTO && stored && objective == 0;
     if (stored && !stored_supported(max_count, K)) return RCD_ERR_UNSUPPORTED;
     int l0 = 0;
     while (l0 < L) {
@@ -1188,7 +1190,7 @@ static int partition_dataset_impl(int objective, const void *X_dev, int dt, int6
                 c.order_out = order_dev;
                 c.out_index = idx + offset[l];
                 c.objective = objective;
-                c.incremental = stored && incremental;
+                c.incremental = stored && (incremental || auto_incremental);
                 if (c.incremental)
                     for (int k = 0; k < K; ++k) c.valid[k] = 1;      // the initial gains (column sums) are current
                 if (stored) {

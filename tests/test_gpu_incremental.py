@@ -152,3 +152,27 @@ def test_incremental_dataset_scaled_workloads(rcd, name, L, n_c, d):
         assign, order, obj = rcd.partition_dataset(dev(ds.X), dev(ds.labels), L, ds.r, ds.sigma2,
                                                    rcd.MODE_INCREMENTAL, ws)
         check_dataset(rcd, ds, assign.cpu().numpy(), order.cpu().numpy(), obj)
+
+
+def test_mode_auto_takes_the_incremental_route_when_s_fits_and_recomputes_when_not(rcd):
+    ds = si.make_dataset(si.WORKLOADS["cifar10"], L=3, n_c=700, d=96)
+    N, K = ds.X.shape[0], len(ds.r)
+    Xd, yd = dev(ds.X), dev(ds.labels)
+    _, full = rcd.dataset_workspace_bytes(N, ds.L, 700, K, rcd.MODE_STORED)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    a0, o0, f0 = rcd.partition_dataset(Xd, yd, ds.L, ds.r, ds.sigma2, rcd.MODE_AUTO, ws)
+    auto_stats = rcd.last_stats()
+    a1, o1, f1 = rcd.partition_dataset(Xd, yd, ds.L, ds.r, ds.sigma2, rcd.MODE_INCREMENTAL, ws)
+    assert torch.equal(a0, a1) and torch.equal(o0, o1) and np.array_equal(f0, f1)
+    now = rcd.last_stats()
+    assert {k: v for k, v in auto_stats.items() if k != "step_ticks"} == {k: v for k, v in now.items() if k != "step_ticks"}
+    check_dataset(rcd, ds, a0.cpu().numpy(), o0.cpu().numpy(), f0)
+    # a workspace too small for any class's S: the same call recomputes S inside the sweeps
+    mn_rc, _ = rcd.dataset_workspace_bytes(N, ds.L, 700, K, rcd.MODE_RECOMPUTE)
+    mn_st, _ = rcd.dataset_workspace_bytes(N, ds.L, 700, K, rcd.MODE_STORED)
+    assert mn_rc < mn_st
+    small = torch.empty(mn_rc, dtype=torch.uint8, device="cuda")
+    a2, o2, f2 = rcd.partition_dataset(Xd, yd, ds.L, ds.r, ds.sigma2, rcd.MODE_AUTO, small)
+    check_dataset(rcd, ds, a2.cpu().numpy(), o2.cpu().numpy(), f2)
+    with pytest.raises(rcd.RcdError):
+        rcd.partition_dataset(Xd, yd, ds.L, ds.r, ds.sigma2, rcd.MODE_STORED, small)
