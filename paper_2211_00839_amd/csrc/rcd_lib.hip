@@ -221,6 +221,8 @@ int fast_setup()
     if (!g_fast_ready) {
         const void *sim_kernels[] = {reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float>),
                                      reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16>),
+                                     reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float, sim::EPI_RBF_MIRROR>),
+                                     reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16, sim::EPI_RBF_MIRROR>),
                                      reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float, sim::EPI_DISTANCE>),
                                      reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16, sim::EPI_DISTANCE>)};
         for (const void *k : sim_kernels)
@@ -632,7 +634,30 @@ int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, 
     else
         hipLaunchKernelGGL(sim::k_row_norms<__bf16>, dim3(nblk), dim3(256), 0, stream, (const __bf16 *)X,
                            (long long)ldx, row_index, (int)n, (int)d, sq);
-    if (fast) {
+    // Only the tiles on and above the diagonal, each also storing its transpose, when the output can take
+    // 16-byte stores along its rows and the k loop is long enough to be worth it: the mirrored stores go out
+    // in 16-byte pieces (about 2 TB/s against 2.7 for whole lines), so this pays once the matrix cores, not
+    // the writes, bound a tile: from about 4096 matrix-core cycles per 256 x 256 tile and wave (measured:
+    // fp32 d = 128 and bf16 d = 2048 gain 1.3x and 1.5x, fp32 d = 64 and bf16 d = 512 lose).
+    // RCD_SIM_MIRROR: 0 never, 1 by that rule, 2 whenever the layout allows.
+    const int64_t tm = (n + sim::pipe::TM - 1) / sim::pipe::TM;
+    const int mirror_mode = env_int("RCD_SIM_MIRROR", 1, 0, 2);
+    const bool mirror = fast && mirror_mode != 0 && (mirror_mode == 2 || (dt == RCD_F32 ? 32 : 2) * d >= 4096) &&
+                        (ncols_pad + sim::pipe::TN - 1) / sim::pipe::TN == tm &&
+                        (reinterpret_cast<uintptr_t>(S) & 15) == 0 && ld_s % 4 == 0;
+    if (mirror) {
+        RCD_TRY(fast_setup());
+        const int64_t tiles = ((tm + 1) / 2) * (tm + 1);
+        const dim3 grid((unsigned)((tiles + 7) / 8 * 8));
+        if (dt == RCD_F32)
+            hipLaunchKernelGGL((sim::k_gram_rbf_fast<float, sim::EPI_RBF_MIRROR>), grid, dim3(sim::THREADS),
+                               sim::pipe::LDS_BYTES, stream, (const float *)X, (long long)ldx, row_index, (int)n, (int)d,
+                               (const float *)sq, exp_scale, S, (long long)ld_s, ncols_pad, (double *)nullptr);
+        else
+            hipLaunchKernelGGL((sim::k_gram_rbf_fast<__bf16, sim::EPI_RBF_MIRROR>), grid, dim3(sim::THREADS),
+                               sim::pipe::LDS_BYTES, stream, (const __bf16 *)X, (long long)ldx, row_index, (int)n, (int)d,
+                               (const float *)sq, exp_scale, S, (long long)ld_s, ncols_pad, (double *)nullptr);
+    } else if (fast) {
         RCD_TRY(fast_setup());
         const int64_t tiles = ((n + sim::pipe::TM - 1) / sim::pipe::TM) * ((ncols_pad + sim::pipe::TN - 1) / sim::pipe::TN);
         const dim3 grid((unsigned)((tiles + 7) / 8 * 8));

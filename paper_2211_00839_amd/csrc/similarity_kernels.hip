@@ -40,12 +40,13 @@ __device__ __forceinline__ float rbf_value(float gram, float sqi_s, float sqj_s,
     return __builtin_amdgcn_fmed3f(fast_exp2(fmaf(gram, scale2, sqi_s + sqj_s)), 0.f, 1.f);
 }
 
-enum { EPI_RBF = 0, EPI_DISTANCE = 1 };
+enum { EPI_RBF = 0, EPI_DISTANCE = 1, EPI_RBF_MIRROR = 2 };
 
-// The L2 distance from the Gram value and the two squared norms, clamped at 0 before the root.
+// The L2 distance from the Gram value and the two squared norms, clamped at 0 before the root
+// (the hardware root, about 1 ulp; squared distances here are far from the denormal range or 0).
 __device__ __forceinline__ float distance_value(float gram, float sqi, float sqj)
 {
-    return __builtin_sqrtf(fmaxf(fmaf(gram, -2.f, sqi + sqj), 0.f));
+    return __builtin_amdgcn_sqrtf(fmaxf(fmaf(gram, -2.f, sqi + sqj), 0.f));
 }
 
 // Sum of one tile's distances over its 256 threads in a fixed order (lanes by butterfly, then the
@@ -476,6 +477,9 @@ __device__ __forceinline__ bool tile_of_workgroup(int w, int nwg, int tiles_m, i
 
 // Gram tile + Gaussian epilogue, fast path.  grid = tiles rounded up to a multiple of 8,
 // dynamic LDS = pipe::LDS_BYTES.  Columns n .. ncols_pad-1 of the output are written as 0.
+// EPI = EPI_RBF_MIRROR: S is symmetric, so only the tiles on and above the diagonal are computed (the same
+// folded tile list as below, same grid) and each one above the diagonal also stores its transpose; needs
+// ncols_pad <= 256 * ceil(n / 256), S 16-byte aligned and lds_out a multiple of 4.
 // EPI = EPI_DISTANCE: nothing is stored; the sum of the tile's distances over its pairs i < j goes to
 // one slot of pair_sums; call with exp_scale = 1, ncols_pad = n and a grid of
 // ((tiles + 1) / 2) * (tiles + 1) workgroups rounded up to a multiple of 8, tiles = ceil(n / 256),
@@ -494,7 +498,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
     const int tiles_m = (n + TM - 1) / TM, tiles_n = (ncols_pad + TN - 1) / TN;
     int ti, tj;
     size_t sum_slot = 0;
-    if constexpr (EPI == EPI_DISTANCE) {
+    if constexpr (EPI != EPI_RBF) {
         // Only tiles on or above the diagonal carry pairs (i < j).  Tile row r (tiles_m - r of them) and
         // tile row tiles_m - 1 - r (r + 1 of them) together fill one row of a (tiles_m + 1)-wide
         // rectangle with (tiles_m + 1) / 2 rows, which is dealt to the workgroups like any tile grid.
@@ -509,7 +513,8 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
             tj = ti + (c - (tiles_m - r));
             if (ti == r) {
                 // odd tile count: the middle tile row has no partner, its slots past the row's end stay empty
-                if (tid == 0) pair_sums[sum_slot] = 0.0;
+                if constexpr (EPI == EPI_DISTANCE)
+                    if (tid == 0) pair_sums[sum_slot] = 0.0;
                 return;
             }
         }
@@ -518,7 +523,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
     }
     const int i0 = ti * TM, j0 = tj * TN;
 
-    if constexpr (EPI == EPI_DISTANCE) {
+    if constexpr (EPI != EPI_RBF) {
         // every tile of the list holds work
     } else if (j0 >= n) {
         // tile entirely in the zero padding of the output pitch
@@ -584,6 +589,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
                         i += (e == 3) ? 5 : 1;
                     }
                     total += (double)part;
+                    asm volatile("" : "+v"(total));      // the sum is taken here, not saved up for the end
                     pin_schedule();
                 }
             }
@@ -596,6 +602,14 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
     float *dst0 = S + (size_t)r0 * lds_out + (j0 + wc * 128 + (lane & 31));
     // one running row pointer per lane: rows advance +1 +1 +1 +5 through the accumulator layout
     const long long step1 = lds_out, step5 = 5 * lds_out;
+    // EPI_RBF_MIRROR: a tile above the diagonal also writes its transpose, S(j,i) = S(i,j): a lane's four
+    // consecutive rows of one column are four consecutive floats of the mirrored row
+    float *mir[4];
+    if constexpr (EPI == EPI_RBF_MIRROR) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) mir[b] = S + (size_t)min(jj[b], n - 1) * lds_out + r0;
+    }
+    const bool mirror = EPI == EPI_RBF_MIRROR && ti != tj;
     auto epilogue = [&](auto plain_tag) {
         constexpr bool PLAIN = decltype(plain_tag)::value;   // interior tile off the diagonal: no checks
         float *dst = dst0;
@@ -607,6 +621,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
                 const int rl = wr * 128 + a * 32 + rq * 8 + (lane >> 5) * 4;
                 const float4 sqi4 = *reinterpret_cast<const float4 *>(sq_rows + rl);
                 const float sqi[4] = {sqi4.x, sqi4.y, sqi4.z, sqi4.w};
+                float col[4][4];        // [b][e]: what goes to the mirrored rows
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
 #pragma unroll
@@ -618,9 +633,26 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
                             if (i == jj[b]) v = 1.f;
                             if (i < n && jj[b] < ncols_pad) dst[b * 32] = jj[b] < n ? v : 0.f;
                         }
+                        col[b][e] = v;
                     }
                     dst += (e == 3) ? step5 : step1;
                     i += (e == 3) ? 5 : 1;
+                }
+                if constexpr (EPI == EPI_RBF_MIRROR) {
+                    if (PLAIN || mirror) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            float *m = mir[b] + (a * 32 + rq * 8);
+                            if constexpr (PLAIN) {
+                                *reinterpret_cast<float4 *>(m) = make_float4(col[b][0], col[b][1], col[b][2], col[b][3]);
+                            } else {
+                                const int ib = i0 + rl;       // the four rows i of this group are the columns here
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (jj[b] < n && ib + e < n) m[e] = col[b][e];
+                            }
+                        }
+                    }
                 }
                 pin_schedule();
             }

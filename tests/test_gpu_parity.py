@@ -76,6 +76,36 @@ def test_similarity_fast_path_edges(rcd, dtype, n, d):
     assert np.all(np.diag(S) == 1.0)
 
 
+@pytest.mark.parametrize("dtype,n,d", [("f32", 1, 32), ("f32", 255, 128), ("f32", 256, 96), ("f32", 257, 32),
+                                       ("f32", 513, 160), ("bf16", 300, 64), ("bf16", 770, 2048), ("f32", 1025, 64),
+                                       ("bf16", 1300, 128), ("f32", 1290, 256)])
+def test_similarity_mirrored_tiles(rcd, monkeypatch, dtype, n, d):
+    """The build that computes only the tiles on and above the diagonal and stores each one's transpose
+    as well: forced on for every shape (it is chosen by itself only for long k loops), it must give the
+    bits of the full build, over odd and even tile counts, ragged edges and a pitched output."""
+    print(f"similarity mirrored tiles {dtype} n={n} d={d}", flush=True)
+    X = si.make_class(seed=950 + n + d, n=n, d=d, dtype=dtype)
+    Xd = dev(X)
+    monkeypatch.setenv("RCD_SIM_MIRROR", "0")
+    full = rcd.similarity(Xd, float(d)).cpu().numpy()
+    monkeypatch.setenv("RCD_SIM_MIRROR", "2")
+    S = rcd.similarity(Xd, float(d)).cpu().numpy()
+    assert np.array_equal(S, full)
+    assert rel_err(S, oracle.similarity(X, float(d))) <= 1e-5
+    assert np.array_equal(S, S.T) and np.all(np.diag(S) == 1.0)
+    # a pitched output: nothing lands past column n, whichever build runs
+    pitch = (n + 3) // 4 * 4 + 8
+    out = torch.full((n, pitch), -7.0, dtype=torch.float32, device="cuda")
+    rcd.similarity(Xd, float(d), out=out[:, :n])
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:, :n], full) and np.all(got[:, n:] == -7.0)
+    # an output whose rows cannot take 16-byte stores falls back to the full build
+    odd = torch.full((n, n + 1), -7.0, dtype=torch.float32, device="cuda")
+    rcd.similarity(Xd, float(d), out=odd[:, :n])
+    got = odd.cpu().numpy()
+    assert np.array_equal(got[:, :n], full) and np.all(got[:, n:] == -7.0)
+
+
 def test_similarity_fast_path_gather_pitched_input_and_output(rcd):
     # aligned rows with a pitch (ld_x > d), a row gather and a pitched output: still the fast path
     n, d = 420, 64
