@@ -211,17 +211,26 @@ __device__ __forceinline__ void sweep_rows(const RcdClass &st, int w, int W, flo
                     }
                 }
             }
-            for (; s < len; s += 256) {
-                const f32x4 m0 = __builtin_nontemporal_load((gcf32x4)(row + s));
+            if (s < len) {
+                // the last, shorter batch (len is a multiple of 256): its pieces in flight together as well
+                f32x4 m[U - 1];
 #pragma unroll
-                for (int i = 0; i < KS; ++i) {
-                    const f32x4 c0 = *(lcf32x4)(lcur + i * JC + s + lane * 4);
-                    if constexpr (KS > 8) {
-                        acc[i].x += (clamp01(m0.x - c0.x) + clamp01(m0.y - c0.y)) +
-                                    (clamp01(m0.z - c0.z) + clamp01(m0.w - c0.w));
-                    } else {
-                        acc[i].x += clamp01(m0.x - c0.x); acc[i].y += clamp01(m0.y - c0.y);
-                        acc[i].z += clamp01(m0.z - c0.z); acc[i].w += clamp01(m0.w - c0.w);
+                for (int u = 0; u < U - 1; ++u)
+                    if (s + 256 * u < len) m[u] = __builtin_nontemporal_load((gcf32x4)(row + s + 256 * u));
+#pragma unroll
+                for (int u = 0; u < U - 1; ++u) {
+                    if (s + 256 * u < len) {
+#pragma unroll
+                        for (int i = 0; i < KS; ++i) {
+                            const f32x4 c0 = *(lcf32x4)(lcur + i * JC + s + 256 * u + lane * 4);
+                            if constexpr (KS > 8) {
+                                acc[i].x += (clamp01(m[u].x - c0.x) + clamp01(m[u].y - c0.y)) +
+                                            (clamp01(m[u].z - c0.z) + clamp01(m[u].w - c0.w));
+                            } else {
+                                acc[i].x += clamp01(m[u].x - c0.x); acc[i].y += clamp01(m[u].y - c0.y);
+                                acc[i].z += clamp01(m[u].z - c0.z); acc[i].w += clamp01(m[u].w - c0.w);
+                            }
+                        }
                     }
                 }
             }
