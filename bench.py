@@ -113,6 +113,24 @@ def extra_kernels(rcd, si, torch):
                      "flops": "executed: 2 * 256 * 256 * d per tile, tiles on and above the diagonal only "
                               "(each also stores its transpose)"},
         "nominal_2n2d_TFLOPs_per_s": 2.0 * n * n * d / (ms * 1e-3) / 1e12}
+    # the same matrix by the full build (every tile computed, nothing mirrored): the matrix-core pipeline alone
+    os.environ["RCD_SIM_MIRROR"] = "0"
+    try:
+        rcd.similarity(Xd, float(d), out=S, workspace=ws)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            rcd.similarity(Xd, float(d), out=S, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["RCD_SIM_MIRROR"]
+    ms_full = e0.elapsed_time(e1) / reps
+    tf_full = 2.0 * tiles * tiles * 256 * 256 * d / (ms_full * 1e-3) / 1e12
+    res["similarity_large_class"]["full_build"] = {
+        "kernel": "sim::k_gram_rbf_fast<bf16, full> (RCD_SIM_MIRROR=0)", "ms": ms_full,
+        "roofline": {"bound": "mfma", "achieved": tf_full, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                     "frac": tf_full / MFMA_PEAK_TFLOPS["bf16"], "flops": "executed: 2 * 256 * 256 * d per tile, every tile"}}
     del S
     # the paper's bandwidth heuristic on the same class: the same Gram tiles, on and above the diagonal only
     bws = torch.empty(rcd.load_library().rcd_bandwidth_workspace_bytes(n), dtype=torch.uint8, device="cuda")

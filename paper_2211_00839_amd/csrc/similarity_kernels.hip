@@ -602,12 +602,21 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
     float *dst0 = S + (size_t)r0 * lds_out + (j0 + wc * 128 + (lane & 31));
     // one running row pointer per lane: rows advance +1 +1 +1 +5 through the accumulator layout
     const long long step1 = lds_out, step5 = 5 * lds_out;
-    // EPI_RBF_MIRROR: a tile above the diagonal also writes its transpose, S(j,i) = S(i,j): a lane's four
-    // consecutive rows of one column are four consecutive floats of the mirrored row
+    // EPI_RBF_MIRROR: a tile above the diagonal also writes its transpose, S(j,i) = S(i,j).  A lane's four
+    // consecutive rows of one column are four consecutive floats of the mirrored row; stored straight
+    // from the registers they would leave as 16-byte pieces of 32 different lines per instruction.  An
+    // interior tile therefore turns each 32-row band of a wave's sub-tile round in LDS (the ring is
+    // idle; a wave has a region of its own, 128 mirrored rows of 32 floats at a pitch of 36) and stores
+    // it as whole 128-byte lines, eight per instruction.  Edge tiles store element by element, checked.
+    constexpr int TP = 36;
     float *mir[4];
+    float *turn = nullptr, *mir_lines = nullptr;
     if constexpr (EPI == EPI_RBF_MIRROR) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) mir[b] = S + (size_t)min(jj[b], n - 1) * lds_out + r0;
+        turn = reinterpret_cast<float *>(lds + 4096) + wave * (128 * TP);
+        // lane -> mirrored row (lane >> 3) of a group of eight, floats 4 (lane & 7) .. + 3 of the band
+        mir_lines = S + (size_t)min(j0 + wc * 128 + (lane >> 3), n - 1) * lds_out + (i0 + wr * 128 + (lane & 7) * 4);
     }
     const bool mirror = EPI == EPI_RBF_MIRROR && ti != tj;
     auto epilogue = [&](auto plain_tag) {
@@ -639,20 +648,31 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
                     i += (e == 3) ? 5 : 1;
                 }
                 if constexpr (EPI == EPI_RBF_MIRROR) {
-                    if (PLAIN || mirror) {
+                    if constexpr (PLAIN) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            *reinterpret_cast<float4 *>(turn + (b * 32 + (lane & 31)) * TP + rq * 8 + (lane >> 5) * 4) =
+                                make_float4(col[b][0], col[b][1], col[b][2], col[b][3]);
+                    } else if (mirror) {
 #pragma unroll
                         for (int b = 0; b < 4; ++b) {
                             float *m = mir[b] + (a * 32 + rq * 8);
-                            if constexpr (PLAIN) {
-                                *reinterpret_cast<float4 *>(m) = make_float4(col[b][0], col[b][1], col[b][2], col[b][3]);
-                            } else {
-                                const int ib = i0 + rl;       // the four rows i of this group are the columns here
+                            const int ib = i0 + rl;       // the four rows i of this group are the columns here
 #pragma unroll
-                                for (int e = 0; e < 4; ++e)
-                                    if (jj[b] < n && ib + e < n) m[e] = col[b][e];
-                            }
+                            for (int e = 0; e < 4; ++e)
+                                if (jj[b] < n && ib + e < n) m[e] = col[b][e];
                         }
                     }
+                }
+                pin_schedule();
+            }
+            if constexpr (EPI == EPI_RBF_MIRROR && PLAIN) {
+                // the band is complete in this wave's region (LDS operations of one wave stay in order)
+                float *out = mir_lines + a * 32;
+#pragma unroll
+                for (int g = 0; g < 16; ++g) {
+                    const float4 line = *reinterpret_cast<const float4 *>(turn + (g * 8 + (lane >> 3)) * TP + (lane & 7) * 4);
+                    *reinterpret_cast<float4 *>(out + (size_t)(g * 8) * lds_out) = line;
                 }
                 pin_schedule();
             }
