@@ -637,7 +637,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
                     for (int b = 0; b < 4; ++b) {
                         float v = rbf_value(acc_read(acc[a][b][rq * 4 + e]), sqi[e], sqj[b], scale2);
                         if constexpr (PLAIN) {
-                            dst[b * 32] = v;
+                            __builtin_nontemporal_store(v, dst + b * 32);
                         } else {
                             if (i == jj[b]) v = 1.f;
                             if (i < n && jj[b] < ncols_pad) dst[b * 32] = jj[b] < n ? v : 0.f;
@@ -672,7 +672,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
 #pragma unroll
                 for (int g = 0; g < 16; ++g) {
                     const float4 line = *reinterpret_cast<const float4 *>(turn + (g * 8 + (lane >> 3)) * TP + (lane & 7) * 4);
-                    *reinterpret_cast<float4 *>(out + (size_t)(g * 8) * lds_out) = line;
+                    __builtin_nontemporal_store(__builtin_bit_cast(f32x4, line), reinterpret_cast<f32x4 *>(out + (size_t)(g * 8) * lds_out));
                 }
                 pin_schedule();
             }
