@@ -70,33 +70,31 @@ rcd_k_inc_init(const RcdClass *__restrict__ classes)
 }
 
 // Apply the pending update lists: for every class, every block with a pending list, every tile of
-// 256 samples v:  G[k][v] += sum over the list of the term above.  The workgroup's 4 waves take a
-// quarter of the list each (in list order) and their sums are added in wave order.
-// grid = (max ld / 256, K, ncls).
+// 1024 samples v:  G[k][v] += sum over the list of the term above, added in list order.  Each of the
+// workgroup's 4 waves takes 256 samples and walks the whole list, eight rows in flight; the four waves
+// read neighbouring kilobytes of the same rows at about the same time.
+// grid = (ceil(max ld / 1024), K, ncls).
 extern "C" __global__ void __launch_bounds__(256)
 rcd_k_inc_update(const RcdClass *__restrict__ classes)
 {
-    __shared__ double sums[4][4][64];
     const RcdClass &st = classes[blockIdx.z];
     const int slot = blockIdx.y;
     if (st.done || slot >= st.nneed) return;
     const int k = st.need[slot];
     const int nd = st.dcount[k];
     const int ld = st.ld;
-    const int v0 = blockIdx.x * 256;
-    if (nd <= 0 || v0 >= ld) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int v0 = blockIdx.x * 1024 + wave * 256;
+    if (nd <= 0 || v0 >= ld) return;
     const cci32 dl = (cci32)(inc_dlist(st) + (size_t)k * ld);
     const ccf32 dold = (ccf32)(inc_dold(st) + (size_t)k * ld);
     const ccf32 cur = (ccf32)(st.cur + (size_t)k * ld);
     const gcf32 M = (gcf32)st.M + v0 + lane * 4;
-    const int q = (nd + 3) >> 2;
-    const int e0 = wave * q, e1 = min(nd, e0 + q);
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    int e = e0;
+    int e = 0;
     constexpr int U = 8;      // rows in flight per wave
-    for (; e + U <= e1; e += U) {
+    for (; e + U <= nd; e += U) {
         f32x4 m[U];
         float cn[U], co[U];
 #pragma unroll
@@ -104,7 +102,7 @@ rcd_k_inc_update(const RcdClass *__restrict__ classes)
             const int j = dl[e + u];
             cn[u] = cur[j];
             co[u] = dold[e + u];
-            m[u] = *(gcf32x4)(M + (size_t)j * ld);
+            m[u] = __builtin_nontemporal_load((gcf32x4)(M + (size_t)j * ld));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -114,26 +112,18 @@ rcd_k_inc_update(const RcdClass *__restrict__ classes)
             acc[3] += inc_term(m[u].w, cn[u], co[u]);
         }
     }
-    for (; e < e1; ++e) {
+    for (; e < nd; ++e) {
         const int j = dl[e];
         const float cn = cur[j], co = dold[e];
-        const f32x4 m = *(gcf32x4)(M + (size_t)j * ld);
+        const f32x4 m = __builtin_nontemporal_load((gcf32x4)(M + (size_t)j * ld));
         acc[0] += inc_term(m.x, cn, co);
         acc[1] += inc_term(m.y, cn, co);
         acc[2] += inc_term(m.z, cn, co);
         acc[3] += inc_term(m.w, cn, co);
     }
+    double *g = inc_gains(st) + (size_t)k * ld + v0 + lane * 4;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) sums[wave][c][lane] = acc[c];
-    __syncthreads();
-    if (wave == 0) {
-        double *g = inc_gains(st) + (size_t)k * ld + v0 + lane * 4;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const double t = ((sums[0][c][lane] + sums[1][c][lane]) + sums[2][c][lane]) + sums[3][c][lane];
-            g[c] += t;
-        }
-    }
+    for (int c = 0; c < 4; ++c) g[c] += acc[c];
 }
 
 namespace {

@@ -352,7 +352,7 @@ struct Lane {
         } else if (incremental) {
             int max_ld = 0;
             for (const RcdClass &c : g->host) max_ld = std::max(max_ld, c.ld);
-            update_grid = dim3((unsigned)(max_ld / 256), (unsigned)first.K, (unsigned)ncls);
+            update_grid = dim3((unsigned)((max_ld + 1023) / 1024), (unsigned)first.K, (unsigned)ncls);
             // initial gains = column sums of S: every coverage vector is 0
             hipLaunchKernelGGL(rcd_k_inc_init, dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls), dim3(256), 0, stream,
                                (const RcdClass *)g->classes_dev);
