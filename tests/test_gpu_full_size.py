@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py
+"""GPU parity at the full sizes of the workloads, in the launch configuration bench.py
 times (rcd_partition_dataset, stored S, all classes advanced together).  The
 oracle cannot replay 50 000 steps of 5000-sample classes in test time, so it
 referees SAMPLED steps: the referee replays the whole GPU trace (cheap state

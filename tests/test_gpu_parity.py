@@ -1,5 +1,5 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
-the same seeded inputs.  Tolerances (BASELINE the benchmark spec): similarity 1e-5
+the same seeded inputs.  Tolerances: similarity 1e-5
 relative for fp32 inputs, 2e-2 for bf16; given the same S the greedy trace must
 equal the oracle's except at steps whose top two oracle gains are within 1e-5
 relative (checked in lock step by the oracle's referee); objectives 1e-4."""
