@@ -343,7 +343,10 @@ struct Lane {
         graph_cut = first.objective == 1;
         incremental = !recompute && !graph_cut && first.incremental != 0;
         gc_max_steps = env_int("RCD_GC_STEPS", 4096, 1, 1 << 20);
-        inc_max_steps = env_int("RCD_INC_STEPS", ncls > 1 ? 32 : 4096, 1, 1 << 20);
+        // classes that share a lane: a class that waits for the update launch waits for every class's call,
+        // so a call is kept to about a third of a millisecond (a step takes about 7 ns per sample)
+        const int shared_steps = std::min(32, std::max(4, 400000 / std::max(max_n, 1)));
+        inc_max_steps = env_int("RCD_INC_STEPS", ncls > 1 ? shared_steps : 4096, 1, 1 << 20);
         inc_small_bytes = env_int("RCD_INC_SMALL_KB", 512, 1, 1 << 20) * 1024;
         if (graph_cut) {
             // initial marginal values = column sums of S without the diagonal
