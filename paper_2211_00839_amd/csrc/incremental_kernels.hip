@@ -27,6 +27,7 @@ namespace {
 
 constexpr double INC_TAKEN = -1.0e300;      // gain entry of a sample that is no longer a candidate
 constexpr double INC_LIVE_ABOVE = -1.0e299; // anything above this is a live candidate's gain
+constexpr int INC_STAGE = 32;               // changed j a wave can hold back in LDS during that single pass
 constexpr int INC_SMALL = 512;              // most rows of an update list that the step loop applies itself (LDS copy of the list)
 
 __device__ __forceinline__ double *inc_gains(const RcdClass &st) { return reinterpret_cast<double *>(st.part); }
@@ -135,6 +136,9 @@ struct IncShared {
     int wcount[RCD_STEP_THREADS / 64];
     int sj[INC_SMALL];
     float sold[INC_SMALL], snew[INC_SMALL];
+    // what a wave found in its j range during the single pass of a short coverage update
+    int stj[RCD_STEP_THREADS / 64][INC_STAGE];
+    float stold[RCD_STEP_THREADS / 64][INC_STAGE], stnew[RCD_STEP_THREADS / 64][INC_STAGE];
 };
 
 // Order-preserving 64-bit key of a double (no NaNs here; -0 is made +0 first so that equal values
@@ -280,26 +284,52 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
         const gcf32 row = M + (size_t)vstar * ld;
         float *cur = d.cur + (size_t)js * ld;
         const int j_begin = wave * seg, j_end = min(ld, j_begin + seg);
-        int cnt = 0;
+        // One pass over the wave's range finds the changed j (ascending: pieces in order, lanes in order,
+        // the four entries of a lane in order) and holds back the first INC_STAGE of them in LDS; most steps
+        // change a handful of entries in all, and then this pass is the only one.
+        int cnt = 0;               // the same in every lane of the wave
+        const unsigned long long below = (1ull << lane) - 1ull;
         for (int s = j_begin + lane * 4; s < j_end; s += 256) {
             const f32x4 m = *(gcf32x4)(row + s);
             const f32x4 c = *(const f32x4 *)(cur + s);
-            cnt += (m.x > c.x) + (m.y > c.y) + (m.z > c.z) + (m.w > c.w);
-        }
+            const bool ch[4] = {m.x > c.x, m.y > c.y, m.z > c.z, m.w > c.w};
+            const unsigned long long b0 = __ballot(ch[0]), b1 = __ballot(ch[1]), b2 = __ballot(ch[2]), b3 = __ballot(ch[3]);
+            if ((b0 | b1 | b2 | b3) == 0ull) continue;
+            int pos = cnt + __popcll(b0 & below) + __popcll(b1 & below) + __popcll(b2 & below) + __popcll(b3 & below);
+            const float mv[4] = {m.x, m.y, m.z, m.w}, cv[4] = {c.x, c.y, c.z, c.w};
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
-        __syncthreads();           // everyone has read wbest / wv of this step
+            for (int q = 0; q < 4; ++q)
+                if (ch[q]) {
+                    if (pos < INC_STAGE) { sh.stj[wave][pos] = s + q; sh.stold[wave][pos] = cv[q]; sh.stnew[wave][pos] = mv[q]; }
+                    ++pos;
+                }
+            cnt += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
+        }
+        __syncthreads();           // everyone has read wkey / wv of this step
         if (lane == 0) sh.wcount[wave] = cnt;
         __syncthreads();
         int base = 0, nd = 0;
+        bool staged = true;        // every wave's entries fit what it held back
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const int c = sh.wcount[w];
             if (w < wave) base += c;
             nd += c;
+            staged = staged && c <= INC_STAGE;
         }
         int32_t *dl = dlist + (size_t)js * ld;
         float *dol = dold + (size_t)js * ld;
+        if (nd <= small && staged) {
+            // short list, all of it in LDS already: put the waves' parts end to end and raise the coverage
+            if (lane < cnt) {
+                const int j = sh.stj[wave][lane];
+                const float nw = sh.stnew[wave][lane];
+                sh.sj[base + lane] = j;
+                sh.sold[base + lane] = sh.stold[wave][lane];
+                sh.snew[base + lane] = nw;
+                cur[j] = nw;
+            }
+        } else
         for (int s = j_begin + lane * 4; s < j_end; s += 256) {
             const f32x4 m = *(gcf32x4)(row + s);
             const f32x4 c = *(const f32x4 *)(cur + s);
