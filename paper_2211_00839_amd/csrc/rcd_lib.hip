@@ -640,12 +640,15 @@ int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, 
     // Only the tiles on and above the diagonal, each also storing its transpose, when the output can take
     // 16-byte stores along its rows and the k loop is long enough to be worth it: the mirrored stores go out
     // in 16-byte pieces (about 2 TB/s against 2.7 for whole lines), so this pays once the matrix cores, not
-    // the writes, bound a tile: from about 4096 matrix-core cycles per 256 x 256 tile and wave (measured:
-    // fp32 d = 128 and bf16 d = 2048 gain 1.3x and 1.5x, fp32 d = 64 and bf16 d = 512 lose).
+    // the writes, bound a tile: from about 2048 matrix-core cycles per 256 x 256 tile and wave (measured:
+    // fp32 d >= 96 and bf16 d >= 1024 gain, up to 1.9x and 1.6x; fp32 d = 64 is even, bf16 d = 512 loses),
+    // and once the full build has more tiles than the chip has compute units (below that the mirrored
+    // build only leaves more of them idle).
     // RCD_SIM_MIRROR: 0 never, 1 by that rule, 2 whenever the layout allows.
     const int64_t tm = (n + sim::pipe::TM - 1) / sim::pipe::TM;
     const int mirror_mode = env_int("RCD_SIM_MIRROR", 1, 0, 2);
-    const bool mirror = fast && mirror_mode != 0 && (mirror_mode == 2 || (dt == RCD_F32 ? 32 : 2) * d >= 4096) &&
+    const bool worth_it = (dt == RCD_F32 ? 32 : 2) * d >= 2048 && sweep_setup() == RCD_OK && tm * tm > g_cu_count;
+    const bool mirror = fast && mirror_mode != 0 && (mirror_mode == 2 || worth_it) &&
                         (ncols_pad + sim::pipe::TN - 1) / sim::pipe::TN == tm &&
                         (reinterpret_cast<uintptr_t>(S) & 15) == 0 && ld_s % 4 == 0;
     if (mirror) {
