@@ -176,3 +176,40 @@ def test_mode_auto_takes_the_incremental_route_when_s_fits_and_recomputes_when_n
     check_dataset(rcd, ds, a2.cpu().numpy(), o2.cpu().numpy(), f2)
     with pytest.raises(rcd.RcdError):
         rcd.partition_dataset(Xd, yd, ds.L, ds.r, ds.sigma2, rcd.MODE_STORED, small)
+
+
+def test_skewed_class_sizes_on_every_route(rcd):
+    # classes of 1, 37, 0, 640 and 1300 samples in one data set (the lanes get very unequal shares, one class is
+    # smaller than K, one is empty): incremental, sweep, recompute and graph-cut routes, each refereed per class
+    sizes = [1, 37, 0, 640, 1300]
+    L, d, r = len(sizes), 64, [1, 2, 1, 3]
+    rng = np.random.default_rng(77)
+    X = si.make_class(seed=78, n=sum(sizes), d=d, G=6)
+    labels = np.repeat(np.arange(L), sizes).astype(np.int32)
+    perm = rng.permutation(len(labels))
+    X, labels = np.ascontiguousarray(X[perm]), np.ascontiguousarray(labels[perm])
+    Xd, yd = dev(X), dev(labels)
+    N, K = len(labels), len(r)
+    _, full = rcd.dataset_workspace_bytes(N, L, max(sizes), K, rcd.MODE_STORED)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    for label, kw in (("incremental", dict(mode=rcd.MODE_INCREMENTAL)), ("sweeps", dict(mode=rcd.MODE_STORED)),
+                      ("recompute", dict(mode=rcd.MODE_RECOMPUTE)), ("graph cut", dict(graph_cut=True))):
+        print(f"  skewed classes, {label}", flush=True)
+        assign, order, obj = rcd.partition_dataset(Xd, yd, L, r, float(d), workspace=ws, **kw)
+        assign, order = assign.cpu().numpy(), order.cpu().numpy()
+        assert np.all(assign >= 0)
+        for c in range(L):
+            idx = np.flatnonzero(labels == c)
+            if len(idx) == 0:
+                assert np.all(obj[c] == 0.0)
+                continue
+            cap = oracle.quota(len(idx), r)
+            S = rcd.similarity(Xd, float(d), row_index=dev(idx.astype(np.int32))).cpu().numpy()
+            a, o = assign[idx], order[idx]
+            assert np.bincount(a, minlength=K).tolist() == cap.tolist()
+            objective = "gc" if label == "graph cut" else "fl"
+            res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, objective=objective)
+            assert res["rc"] == 0 and res["checked"] == len(idx), (label, c, res)
+            for k in range(K):
+                ref = oracle.f_value(S, np.flatnonzero(a == k), objective)
+                assert abs(obj[c, k] - ref) <= 1e-4 * max(ref, 1e-30) + 1e-9, (label, c, k, obj[c, k], ref)
