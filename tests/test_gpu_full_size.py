@@ -381,3 +381,39 @@ def test_whole_data_set_greedmax_incremental(rcd):
     # without the class split nothing balances the labels: the shards' class counts are no longer the quotas
     per = np.stack([np.bincount(ds.labels[a == k], minlength=ds.L) for k in range(K)])
     print(f"  class counts per worker without the class split:\n{per}", flush=True)
+
+
+@pytest.mark.parametrize("route", ["incremental", "sweeps", "graph_cut"])
+def test_sixteen_blocks_on_a_12000_sample_class(rcd, route):
+    # the largest block count on a class of 47 tiles of 256: every step taken, sampled steps refereed
+    print(f"K = 16, n = 12000, {route}", flush=True)
+    n, d = 12000, 128
+    r = [3, 1, 4, 1, 2, 2, 1, 3, 4, 4, 1, 2, 3, 3, 2, 1]
+    X = si.make_class(seed=91, n=n, d=d, G=8)
+    S = rcd.similarity(dev(X), float(d))
+    cap = oracle.quota(n, r)
+    import os
+    old = os.environ.get("RCD_INCREMENTAL")
+    os.environ["RCD_INCREMENTAL"] = "1" if route == "incremental" else "0"
+    try:
+        if route == "graph_cut":
+            a, o, f = rcd.partition_class_graph_cut(S, cap)
+        else:
+            a, o, f = rcd.partition_class(S=S, cap=cap)
+    finally:
+        if old is None:
+            del os.environ["RCD_INCREMENTAL"]
+        else:
+            os.environ["RCD_INCREMENTAL"] = old
+    a, o = a.cpu().numpy(), o.cpu().numpy()
+    assert np.bincount(a, minlength=16).tolist() == cap.tolist()
+    assert np.array_equal(np.sort(o), np.arange(n))
+    Sh = S.cpu().numpy()
+    objective = "gc" if route == "graph_cut" else "fl"
+    steps = [0, 1, 15, 16, 17, 100, 3000, 6000, 11000, 11998, 11999]
+    res = oracle.lockstep(Sh, cap, o, a, rel_tol=1e-5, check=steps, objective=objective)
+    print(f"  referee {res}", flush=True)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
+    for k in (0, 2, 15):
+        ref = oracle.f_value(Sh, np.flatnonzero(a == k), objective)
+        assert abs(f[k] - ref) <= 1e-4 * ref + 1e-9
