@@ -305,8 +305,7 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
                 }
             cnt += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
         }
-        __syncthreads();           // everyone has read wkey / wv of this step
-        if (lane == 0) sh.wcount[wave] = cnt;
+        if (lane == 0) sh.wcount[wave] = cnt;      // last read before the barrier that ended the previous step
         __syncthreads();
         int base = 0, nd = 0;
         bool staged = true;        // every wave's entries fit what it held back
@@ -507,7 +506,7 @@ rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
         best = inc_value(key);
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }
-        __syncthreads();           // everyone has read wbest / wv and the block state of this step
+        // (every thread chose js from the block state before the barrier above: it may change now)
         if (tid == 0) {
             d.cnt[js] += 1;
             d.f[js] += best;
@@ -541,8 +540,10 @@ rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
                 }
             }
         }
-        __syncthreads();           // the row update is done before v* is struck out (both touch g[v*])
-        if (tid < K) G[(size_t)tid * ld + vstar] = INC_TAKEN;
+        // v* leaves every block's candidates; in the served block the thread that has just updated that
+        // entry strikes it out (its own earlier store to the same address: no barrier in between is needed)
+        if ((vstar >> 2) % NT == tid) g[vstar] = INC_TAKEN;
+        if (tid < K && tid != js) G[(size_t)tid * ld + vstar] = INC_TAKEN;
         useful += nR;
         nR -= 1;
         ++t;
