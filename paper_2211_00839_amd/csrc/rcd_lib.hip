@@ -227,6 +227,13 @@ int fast_setup()
                                      reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16, sim::EPI_DISTANCE>)};
         for (const void *k : sim_kernels)
             HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, sim::pipe::LDS_BYTES));
+        const void *batch_kernels[] = {
+            reinterpret_cast<const void *>(&sim::k_gram_rbf_fast_batch<float, sim::EPI_RBF>),
+            reinterpret_cast<const void *>(&sim::k_gram_rbf_fast_batch<__bf16, sim::EPI_RBF>),
+            reinterpret_cast<const void *>(&sim::k_gram_rbf_fast_batch<float, sim::EPI_RBF_MIRROR>),
+            reinterpret_cast<const void *>(&sim::k_gram_rbf_fast_batch<__bf16, sim::EPI_RBF_MIRROR>)};
+        for (const void *k : batch_kernels)
+            HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, sim::pipe::LDS_BYTES));
         const void *rc_kernels[] = {reinterpret_cast<const void *>(&rcd_k_round_rc_fast<float, true>),
                                     reinterpret_cast<const void *>(&rcd_k_round_rc_fast<float, false>),
                                     reinterpret_cast<const void *>(&rcd_k_round_rc_fast<__bf16, true>),
@@ -625,6 +632,15 @@ bool carve_group_fixed(Carver &cv, Group &g, int ncls, int K)
     return !cv.fail;
 }
 
+// The mirrored build is asked for (RCD_SIM_MIRROR = 2), or pays: tiles_in_flight = tiles of the full build
+// that the launch holds.
+bool mirror_wanted(int dt, int64_t d, int64_t tiles_in_flight)
+{
+    const int mode = env_int("RCD_SIM_MIRROR", 1, 0, 2);
+    if (mode != 1) return mode == 2;
+    return (dt == RCD_F32 ? 32 : 2) * d >= 2048 && sweep_setup() == RCD_OK && tiles_in_flight > g_cu_count;
+}
+
 int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, const int32_t *row_index,
                       float sigma2, float *S, int64_t ld_s, int ncols_pad, float *sq, hipStream_t stream)
 {
@@ -646,9 +662,7 @@ int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, 
     // build only leaves more of them idle).
     // RCD_SIM_MIRROR: 0 never, 1 by that rule, 2 whenever the layout allows.
     const int64_t tm = (n + sim::pipe::TM - 1) / sim::pipe::TM;
-    const int mirror_mode = env_int("RCD_SIM_MIRROR", 1, 0, 2);
-    const bool worth_it = (dt == RCD_F32 ? 32 : 2) * d >= 2048 && sweep_setup() == RCD_OK && tm * tm > g_cu_count;
-    const bool mirror = fast && mirror_mode != 0 && (mirror_mode == 2 || worth_it) &&
+    const bool mirror = fast && mirror_wanted(dt, d, tm * tm) &&
                         (ncols_pad + sim::pipe::TN - 1) / sim::pipe::TN == tm &&
                         (reinterpret_cast<uintptr_t>(S) & 15) == 0 && ld_s % 4 == 0;
     if (mirror) {
@@ -713,6 +727,86 @@ int launch_row_norms(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, c
         hipLaunchKernelGGL(sim::k_row_norms<__bf16>, dim3(nblk), dim3(256), 0, stream, (const __bf16 *)X,
                            (long long)ldx, row_index, (int)n, (int)d, sq);
     HIP_TRY(hipGetLastError());
+    return RCD_OK;
+}
+
+// One class of a data set whose similarity matrix is to be built into its descriptor's M.
+struct SimRequest {
+    const int32_t *row_index;
+    int64_t n;
+    float *S;
+    int64_t ld;
+    float *sq;
+};
+
+// Similarity matrices of several classes over the same features.  Rows that fit the fast path: all the
+// row norms in one launch and all the tiles in one launch per 64 classes, so that classes of a few tiles
+// fill the chip together; otherwise one pair of launches per class.
+int launch_similarity_batch(const void *X, int dt, int64_t d, int64_t ldx, float sigma2,
+                            const std::vector<SimRequest> &req, hipStream_t stream)
+{
+    if (req.empty()) return RCD_OK;
+    if (!rows_fit_fast_path(X, dt, d, ldx) || req.size() == 1 || env_int("RCD_SIM_BATCH", 1, 0, 1) == 0) {
+        for (const SimRequest &q : req)
+            RCD_TRY(launch_similarity(X, dt, q.n, d, ldx, q.row_index, sigma2, q.S, q.ld, (int)q.ld, q.sq, stream));
+        return RCD_OK;
+    }
+    RCD_TRY(fast_setup());
+    const float exp_scale = (float)(-1.4426950408889634 / (2.0 * (double)sigma2));
+    int64_t all_tiles = 0;
+    for (const SimRequest &q : req) {
+        const int64_t tm = (q.n + sim::pipe::TM - 1) / sim::pipe::TM;
+        all_tiles += tm * tm;
+    }
+    const bool mirror = mirror_wanted(dt, d, all_tiles);
+    for (size_t first = 0; first < req.size(); first += sim::SIM_BATCH) {
+        sim::SimBatch b;
+        memset(&b, 0, sizeof b);
+        b.njobs = (int)std::min<size_t>(sim::SIM_BATCH, req.size() - first);
+        int64_t wgs = 0, row_wgs = 0;
+        for (int j = 0; j < b.njobs; ++j) {
+            const SimRequest &q = req[first + j];
+            const int64_t tm = (q.n + sim::pipe::TM - 1) / sim::pipe::TM;
+            const int64_t tiles = mirror ? ((tm + 1) / 2) * (tm + 1) : tm * ((q.ld + sim::pipe::TN - 1) / sim::pipe::TN);
+            sim::SimJob &job = b.job[j];
+            job.row_index = q.row_index;
+            job.sq = q.sq;
+            job.S = q.S;
+            job.lds_out = q.ld;
+            job.n = (int)q.n;
+            job.ncols_pad = (int)q.ld;
+            job.wg_begin = (int)wgs;
+            job.wg_count = (int)((tiles + 7) / 8 * 8);
+            job.row_wg_begin = (int)row_wgs;
+            wgs += job.wg_count;
+            row_wgs += (q.n + 3) / 4;
+            if (wgs > 0x7fffffff || row_wgs > 0x7fffffff) return RCD_ERR_UNSUPPORTED;
+        }
+        if (dt == RCD_F32) {
+            hipLaunchKernelGGL(sim::k_row_norms_batch<float>, dim3((unsigned)row_wgs), dim3(256), 0, stream,
+                               (const float *)X, (long long)ldx, (int)d, b);
+            if (mirror)
+                hipLaunchKernelGGL((sim::k_gram_rbf_fast_batch<float, sim::EPI_RBF_MIRROR>), dim3((unsigned)wgs),
+                                   dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream, (const float *)X, (long long)ldx,
+                                   (int)d, exp_scale, b);
+            else
+                hipLaunchKernelGGL((sim::k_gram_rbf_fast_batch<float, sim::EPI_RBF>), dim3((unsigned)wgs),
+                                   dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream, (const float *)X, (long long)ldx,
+                                   (int)d, exp_scale, b);
+        } else {
+            hipLaunchKernelGGL(sim::k_row_norms_batch<__bf16>, dim3((unsigned)row_wgs), dim3(256), 0, stream,
+                               (const __bf16 *)X, (long long)ldx, (int)d, b);
+            if (mirror)
+                hipLaunchKernelGGL((sim::k_gram_rbf_fast_batch<__bf16, sim::EPI_RBF_MIRROR>), dim3((unsigned)wgs),
+                                   dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream, (const __bf16 *)X, (long long)ldx,
+                                   (int)d, exp_scale, b);
+            else
+                hipLaunchKernelGGL((sim::k_gram_rbf_fast_batch<__bf16, sim::EPI_RBF>), dim3((unsigned)wgs),
+                                   dim3(sim::THREADS), sim::pipe::LDS_BYTES, stream, (const __bf16 *)X, (long long)ldx,
+                                   (int)d, exp_scale, b);
+        }
+        HIP_TRY(hipGetLastError());
+    }
     return RCD_OK;
 }
 
@@ -1213,6 +1307,7 @@ static int partition_dataset_impl(int objective, const void *X_dev, int dt, int6
                 HIP_TRY(hipEventCreate(&sim_ev[1]));
                 HIP_TRY(hipEventRecord(sim_ev[0], stream));
             }
+            std::vector<SimRequest> sim_requests;
             for (int l = l0; l < l1; ++l) {
                 if (count[l] == 0) continue;
                 RcdClass &c = g.host[gi];
@@ -1227,14 +1322,14 @@ static int partition_dataset_impl(int objective, const void *X_dev, int dt, int6
                 if (stored) {
                     float *sq = gc.take<float>((size_t)count[l]);
                     if (gc.fail) return RCD_ERR_WORKSPACE;
-                    RCD_TRY(launch_similarity(X_dev, dt, count[l], d, ld_x, idx + offset[l], sigma2, c.M, c.ld, c.ld,
-                                              sq, stream));
+                    sim_requests.push_back(SimRequest{idx + offset[l], count[l], c.M, c.ld, sq});
                 } else {
                     set_recompute_source(c, X_dev, dt, d, ld_x, idx + offset[l], sigma2);
                     RCD_TRY(launch_row_norms(X_dev, dt, count[l], d, ld_x, idx + offset[l], c.sq, stream));
                 }
                 cls_of[gi++] = l;
             }
+            RCD_TRY(launch_similarity_batch(X_dev, dt, d, ld_x, sigma2, sim_requests, stream));
             if (g_profile_on) HIP_TRY(hipEventRecord(sim_ev[1], stream));
             // Stored mode: deal the classes to a few lanes of about equal work (cost ~ n^3),
             // contiguous in the descriptor array.  A recomputed sweep keeps the matrix cores

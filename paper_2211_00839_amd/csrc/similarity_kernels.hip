@@ -484,11 +484,12 @@ __device__ __forceinline__ bool tile_of_workgroup(int w, int nwg, int tiles_m, i
 // one slot of pair_sums; call with exp_scale = 1, ncols_pad = n and a grid of
 // ((tiles + 1) / 2) * (tiles + 1) workgroups rounded up to a multiple of 8, tiles = ceil(n / 256),
 // which is also the number of slots.
-template <typename T, int EPI = EPI_RBF>
-__global__ void __launch_bounds__(THREADS, 1)
-k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
-                const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
-                int ncols_pad, double *__restrict__ pair_sums)
+// The body: workgroup `wg` of the `nwg` that share one matrix (a launch may hold several matrices).
+template <typename T, int EPI>
+__device__ __forceinline__ void
+gram_rbf_fast_tile(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
+                   const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
+                   int ncols_pad, double *__restrict__ pair_sums, int wg, int nwg)
 {
     using namespace pipe;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -503,7 +504,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
         // tile row tiles_m - 1 - r (r + 1 of them) together fill one row of a (tiles_m + 1)-wide
         // rectangle with (tiles_m + 1) / 2 rows, which is dealt to the workgroups like any tile grid.
         int r, c;
-        if (!tile_of_workgroup((int)blockIdx.x, (int)gridDim.x, (tiles_m + 1) / 2, tiles_m + 1, &r, &c)) return;
+        if (!tile_of_workgroup(wg, nwg, (tiles_m + 1) / 2, tiles_m + 1, &r, &c)) return;
         sum_slot = (size_t)r * (tiles_m + 1) + c;
         if (c < tiles_m - r) {
             ti = r;
@@ -519,7 +520,7 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
             }
         }
     } else {
-        if (!tile_of_workgroup((int)blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, &ti, &tj)) return;
+        if (!tile_of_workgroup(wg, nwg, tiles_m, tiles_n, &ti, &tj)) return;
     }
     const int i0 = ti * TM, j0 = tj * TN;
 
@@ -680,6 +681,71 @@ k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restric
     };
     if (i0 + TM <= n && j0 + TN <= n && ti != tj) epilogue(std::true_type{});
     else epilogue(std::false_type{});
+}
+
+template <typename T, int EPI = EPI_RBF>
+__global__ void __launch_bounds__(THREADS, 1)
+k_gram_rbf_fast(const T *__restrict__ X, long long ldx, const int32_t *__restrict__ row_index, int n, int d,
+                const float *__restrict__ sq, float exp_scale, float *__restrict__ S, long long lds_out,
+                int ncols_pad, double *__restrict__ pair_sums)
+{
+    gram_rbf_fast_tile<T, EPI>(X, ldx, row_index, n, d, sq, exp_scale, S, lds_out, ncols_pad, pair_sums,
+                               (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Several similarity matrices over the same feature matrix in one launch (the classes of a data set: a
+// class of a few hundred samples is a handful of tiles, and one launch per class would leave the chip
+// idle).  The jobs travel in the kernel arguments.  Job j owns workgroups wg_begin .. wg_begin + wg_count
+// (both multiples of 8, so a job's workgroups meet the XCDs the way a launch of its own would) and, in
+// the row-norm launch, workgroups row_wg_begin .. of four rows each.
+constexpr int SIM_BATCH = 64;
+struct SimJob {
+    const int32_t *row_index;
+    float *sq;
+    float *S;
+    long long lds_out;
+    int n, ncols_pad;
+    int wg_begin, wg_count;
+    int row_wg_begin, pad_;
+};
+struct SimBatch {
+    SimJob job[SIM_BATCH];
+    int njobs;
+};
+
+template <typename T, int EPI>
+__global__ void __launch_bounds__(THREADS, 1)
+k_gram_rbf_fast_batch(const T *__restrict__ X, long long ldx, int d, float exp_scale, const SimBatch b)
+{
+    const int wg = (int)blockIdx.x;
+    int j = 0;
+    while (j + 1 < b.njobs && wg >= b.job[j + 1].wg_begin) ++j;
+    const SimJob &q = b.job[j];
+    gram_rbf_fast_tile<T, EPI>(X, ldx, q.row_index, q.n, d, q.sq, exp_scale, q.S, q.lds_out, q.ncols_pad, nullptr,
+                               wg - q.wg_begin, q.wg_count);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_row_norms_batch(const T *__restrict__ X, long long ldx, int d, const SimBatch b)
+{
+    const int wg = (int)blockIdx.x;
+    int j = 0;
+    while (j + 1 < b.njobs && wg >= b.job[j + 1].row_wg_begin) ++j;
+    const SimJob &q = b.job[j];
+    const int lane = threadIdx.x & 63;
+    const int i = (wg - q.row_wg_begin) * 4 + (threadIdx.x >> 6);
+    if (i >= q.n) return;
+    const int r = q.row_index ? q.row_index[i] : i;
+    const T *p = X + (size_t)r * ldx;
+    double a = 0.0;
+    for (int t = lane; t < d; t += 64) {
+        const double v = (double)to_f32(p[t]);
+        a += v * v;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off);
+    if (lane == 0) q.sq[i] = (float)a;
 }
 
 // Gram tile + Gaussian epilogue, general path (any alignment, any d).  grid = (column tiles, row tiles).
