@@ -123,3 +123,54 @@ def test_python_binding_refuses_cpu_tensors(lib):
 
     with pytest.raises(rcd.RcdError):
         rcd.similarity(torch.zeros(4, 4), 1.0, workspace=torch.zeros(256, dtype=torch.uint8))
+
+
+def test_argument_validation_of_the_later_entry_points(lib):
+    # graph cut, bandwidth, worker shards, batch sizes: every refusal below happens before any GPU call
+    vp = ctypes.c_void_p
+    obj = np.zeros(2)
+    objp = obj.ctypes.data_as(vp)
+    cap = np.array([1, 1], dtype=np.int64)
+    gc = lib.rcd_partition_class_graph_cut
+    assert gc(None, 10, 10, 2, cap.ctypes.data_as(vp), None, None, objp, None, 0, None) == 1           # no S
+    assert gc(None, 0, 0, 2, np.zeros(2, dtype=np.int64).ctypes.data_as(vp), None, None, objp, None, 0, None) == 0   # empty class
+    assert gc(None, 10, 10, 17, np.ones(17, dtype=np.int64).ctypes.data_as(vp), None, None,
+              np.zeros(17).ctypes.data_as(vp), None, 0, None) in (1, 4)                                 # no S / K too large
+    over = np.array([6, 6], dtype=np.int64)
+    assert gc(ctypes.c_void_p(256), 10, 10, 2, over.ctypes.data_as(vp), None, None, objp, None, 0, None) == 3   # quotas above n
+    r = np.array([1, 0], dtype=np.int32)
+    dsgc = lib.rcd_partition_dataset_graph_cut
+    assert dsgc(None, 0, 10, 4, 4, None, 2, r.ctypes.data_as(vp), 2, 1.0, None, None,
+                np.zeros(4).ctypes.data_as(vp), None, 0, None) == 3                                     # capacity < 1
+    r = np.array([1, 1], dtype=np.int32)
+    assert dsgc(None, 0, 10, 4, 4, None, 2, r.ctypes.data_as(vp), 2, -1.0, None, None,
+                np.zeros(4).ctypes.data_as(vp), None, 0, None) == 1                                     # sigma2 <= 0
+
+    sigma = np.zeros(1)
+    sp = sigma.ctypes.data_as(vp)
+    bw = lib.rcd_bandwidth
+    assert bw(None, 7, 4, 4, 4, None, sp, None, 0, None) == 4             # dtype
+    assert bw(None, 0, 4, 4, 2, None, sp, None, 0, None) == 1             # ld_x < d
+    assert bw(None, 0, 4, 4, 4, None, None, None, 0, None) == 1           # nowhere to put sigma
+    assert bw(None, 0, 4, 4, 4, None, sp, None, 0, None) == 1             # no X
+    assert bw(None, 0, 0, 4, 4, None, sp, None, 0, None) == 0 and sigma[0] == 0.0     # empty set
+    assert lib.rcd_bandwidth_workspace_bytes(0) == 0
+    prev = 0
+    for n in (1, 255, 256, 257, 5000, 50000):
+        b = lib.rcd_bandwidth_workspace_bytes(n)
+        assert b % 256 == 0 and b > prev and b >= 4 * n
+        prev = b
+
+    off = np.zeros(5, dtype=np.int64)
+    sh = lib.rcd_worker_shards
+    assert sh(None, 10, 17, None, off.ctypes.data_as(vp), None, 0, None) == 4          # too many workers
+    assert sh(None, 10, 4, None, None, None, 0, None) == 1                             # no offsets
+    assert sh(None, 10, 4, None, off.ctypes.data_as(vp), None, 0, None) == 1           # no assignment
+    assert sh(None, 0, 4, None, off.ctypes.data_as(vp), None, 0, None) == 0 and off.tolist() == [0] * 5
+    assert lib.rcd_worker_shards_workspace_bytes(0, 4) == 0
+    assert lib.rcd_worker_shards_workspace_bytes(50000, 4) % 256 == 0
+
+    assert rcd.batch_sizes(64, [1, 1, 2, 4]).tolist() == oracle.batch_sizes(64, [1, 1, 2, 4]).tolist()
+    for B, rr in ((0, [1, 2]), (8, [1, 0])):
+        with pytest.raises(rcd.RcdError):
+            rcd.batch_sizes(B, rr)
