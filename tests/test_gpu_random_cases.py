@@ -73,3 +73,57 @@ def test_random_class_on_every_route(rcd, monkeypatch, seed):
         for k in range(K):
             ref = oracle.f_value(S, np.flatnonzero(a == k), objective)
             assert abs(f[k] - ref) <= 1e-4 * max(ref, 0.0) + 1e-12 * scale, (name, k, f[k], ref)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_data_set(rcd, seed):
+    """Random class structure through the data-set entry point: 1 to 150 classes of very unequal sizes (some
+    empty), f32 or bf16 features with a row pitch, a random route and either workspace size; every class
+    refereed at every step on the library's own similarity of that class."""
+    rng = np.random.default_rng(5000 + seed)
+    L = int(rng.choice([1, 2, 7, 40, 70, 150]))
+    sizes = rng.integers(0, int(rng.choice([6, 60, 300])) + 1, size=L)
+    sizes[int(rng.integers(0, L))] = int(rng.integers(1, 700))          # one class larger than the rest
+    N = int(sizes.sum())
+    K = int(rng.integers(1, 9))
+    r = rng.integers(1, 5, size=K)
+    dtype = str(rng.choice(["f32", "bf16"]))
+    d = int(rng.choice([32, 64, 128]))
+    X = si.make_class(seed=6000 + seed, n=N, d=d, G=5, dtype=dtype)
+    labels = np.repeat(np.arange(L), sizes).astype(np.int32)
+    perm = rng.permutation(N)
+    X, labels = np.ascontiguousarray(X[perm]), np.ascontiguousarray(labels[perm])
+    route = str(rng.choice(["sweeps", "incremental", "recompute", "graph cut", "auto"]))
+    print(f"random data set {seed}: L={L} N={N} largest class {int(sizes.max())} K={K} {dtype} d={d} {route}", flush=True)
+    wide = np.zeros((N, d + 16), dtype=X.dtype)
+    wide[:, :d] = X
+    if dtype == "bf16":
+        Xd = torch.from_numpy(wide.view(np.int16)).cuda().view(torch.bfloat16)[:, :d]
+    else:
+        Xd = torch.from_numpy(wide).cuda()[:, :d]
+    yd = torch.from_numpy(labels).cuda()
+    mode = {"sweeps": rcd.MODE_STORED, "incremental": rcd.MODE_INCREMENTAL, "recompute": rcd.MODE_RECOMPUTE,
+            "graph cut": rcd.MODE_STORED, "auto": rcd.MODE_AUTO}[route]
+    mn, full = rcd.dataset_workspace_bytes(N, L, int(sizes.max()), K, rcd.MODE_RECOMPUTE if route == "recompute" else rcd.MODE_STORED)
+    ws = torch.empty(full if rng.random() < 0.5 else mn, dtype=torch.uint8, device="cuda")
+    assign, order, obj = rcd.partition_dataset(Xd, yd, L, r, float(d), mode, ws, graph_cut=route == "graph cut")
+    assign, order = assign.cpu().numpy(), order.cpu().numpy()
+    assert np.all(assign >= 0) and np.all(assign < K)
+    objective = "gc" if route == "graph cut" else "fl"
+    for c in range(L):
+        idx = np.flatnonzero(labels == c)
+        if len(idx) == 0:
+            assert np.all(obj[c] == 0.0)
+            continue
+        cap = oracle.quota(len(idx), r)
+        S = rcd.similarity(Xd, float(d), row_index=torch.from_numpy(idx.astype(np.int32)).cuda()).cpu().numpy()
+        ref = oracle.similarity(X[idx], float(d))
+        assert np.max(np.abs(S - ref) / np.maximum(ref, 1e-30)) <= (1e-5 if dtype == "f32" else 2e-2)
+        a, o = assign[idx], order[idx]
+        assert np.bincount(a, minlength=K).tolist() == cap.tolist()
+        res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, objective=objective)
+        assert res["rc"] == 0 and res["checked"] == len(idx), (c, res)
+        scale = max(1.0, float(S.astype(np.float64).sum()) / K)
+        for k in range(K):
+            want = oracle.f_value(S, np.flatnonzero(a == k), objective)
+            assert abs(obj[c, k] - want) <= 1e-4 * max(want, 0.0) + 1e-12 * scale, (c, k, obj[c, k], want)
