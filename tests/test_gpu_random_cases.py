@@ -127,3 +127,45 @@ def test_random_data_set(rcd, seed):
         for k in range(K):
             want = oracle.f_value(S, np.flatnonzero(a == k), objective)
             assert abs(obj[c, k] - want) <= 1e-4 * max(want, 0.0) + 1e-12 * scale, (c, k, obj[c, k], want)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_similarity_and_bandwidth_shapes(rcd, monkeypatch, seed):
+    """Random shapes through rcd_similarity and rcd_bandwidth: any d (whole 128-byte lines or not), rows with a
+    pitch and an offset that may break the 16-byte alignment, a row gather, an output pitch that may or may not
+    take 16-byte stores, the mirrored build forced on or off or left to the rule."""
+    rng = np.random.default_rng(9000 + seed)
+    dtype = str(rng.choice(["f32", "bf16"]))
+    n_all = int(rng.integers(1, 1500))
+    d = int(rng.choice([1, 7, 31, 32, 48, 64, 96, 100, 128, 200, 256, 300]))
+    off = int(rng.choice([0, 0, 1, 4, 8]))
+    pitch = d + off + int(rng.choice([0, 3, 8, 32]))
+    X = si.make_class(seed=9100 + seed, n=n_all, d=d, G=4, dtype=dtype)
+    wide = np.zeros((n_all, pitch), dtype=X.dtype)
+    wide[:, off:off + d] = X
+    if dtype == "bf16":
+        Xd = torch.from_numpy(wide.view(np.int16)).cuda().view(torch.bfloat16)[:, off:off + d]
+    else:
+        Xd = torch.from_numpy(wide).cuda()[:, off:off + d]
+    gather = rng.random() < 0.5
+    idx = np.sort(rng.choice(n_all, size=int(rng.integers(1, n_all + 1)), replace=False)).astype(np.int32) if gather \
+        else np.arange(n_all, dtype=np.int32)
+    n = len(idx)
+    sigma2 = float(d) * float(rng.choice([0.5, 1.0, 3.0]))
+    out_pitch = n + int(rng.choice([0, 1, 4, 12]))
+    mirror = str(rng.choice(["0", "1", "2"]))
+    monkeypatch.setenv("RCD_SIM_MIRROR", mirror)
+    print(f"random similarity {seed}: {dtype} rows {n} of {n_all} d={d} offset {off} pitch {pitch} out pitch {out_pitch} "
+          f"mirror {mirror} gather {gather}", flush=True)
+    out = torch.full((n, out_pitch), -7.0, dtype=torch.float32, device="cuda")
+    rcd.similarity(Xd, sigma2, row_index=torch.from_numpy(idx).cuda() if gather else None, out=out[:, :n])
+    got = out.cpu().numpy()
+    ref = oracle.similarity(X[idx], sigma2)
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    assert np.max(np.abs(got[:, :n] - ref) / np.maximum(ref, 1e-30)) <= tol
+    assert np.array_equal(got[:, :n], got[:, :n].T) and np.all(np.diag(got[:, :n]) == 1.0)
+    assert np.all(got[:, n:] == -7.0)
+    sigma = rcd.bandwidth(Xd, row_index=torch.from_numpy(idx).cuda() if gather else None)
+    want = oracle.bandwidth(X[idx])
+    # distances between near-identical rows carry the Gram identity's cancellation (absolute ~3e-4 |x| per pair)
+    assert sigma == pytest.approx(want, rel=1e-5, abs=1e-5 * float(np.sqrt(d)))
