@@ -572,7 +572,11 @@ int oracle_partition_dataset(const void *X, int dtype, int64_t N, int64_t d, int
  * f(A u {v}) - f(A), lowest index on ties, a block leaves J once its quota is met).
  * f is not monotone: a marginal value can be negative, and the sample with the largest one
  * is still taken, because the quotas have to be met (Algorithm 1 has no sign test).
- * Readings: f(empty) = 0 (empty sum); sim is used as printed, S[v][a] = sim(v, a).
+ * Readings: f(empty) = 0 (empty sum).  oracle_f_gc evaluates the definition with sim used as
+ * printed, S[v][a] = sim(v, a) with v outside A and a inside, on any S.  Section 4's similarity is
+ * a function of the distance between two samples, hence symmetric; the greedy and its referee
+ * below take that as a precondition: they return -2 for an S that is not exactly symmetric, and
+ * read sim(v, u) as S[u][v].
  * ====================================================================================== */
 
 /* f(A) from the definition; members[m] lists A. */
@@ -596,12 +600,24 @@ double oracle_f_gc(const float *S, int64_t lds, int64_t n, const int32_t *member
     return total;
 }
 
+/* 1 if S[i][j] == S[j][i] for all i, j < n, else 0. */
+static int is_symmetric(const float *S, int64_t lds, int64_t n)
+{
+    /* every pair once, walked in 64 x 64 squares so that a 50 000 x 50 000 matrix stays in cache */
+    for (int64_t i0 = 0; i0 < n; i0 += 64)
+        for (int64_t j0 = i0; j0 < n; j0 += 64)
+            for (int64_t i = i0; i < i0 + 64 && i < n; ++i)
+                for (int64_t j = (j0 > i ? j0 : i + 1); j < j0 + 64 && j < n; ++j)
+                    if (S[i * lds + j] != S[j * lds + i])
+                        return 0;
+    return 1;
+}
+
 /* f(A u {u}) - f(A) for the block whose members are the v with assign[v] == k:
  * u leaves V \ A, so its own terms sum_{a in A} sim(u, a) go, and u enters A, so the
  * terms sum_{v outside A, v != u} sim(v, u) come in.  (tests pin this against the
- * definition above evaluated twice.)  Section 4's similarity is a function of the distance
- * between two samples, hence symmetric: sim(v, u) is read from row u, S[u][v], so that a
- * marginal value walks one row of S (callers pass a symmetric S). */
+ * definition above evaluated twice.)  S is symmetric here (checked by the two callers),
+ * so sim(v, u) = S[v][u] = S[u][v] and both sums walk row u. */
 static double gain_of_gc(const float *S, int64_t lds, int64_t n, const int32_t *assign, int k, int64_t u)
 {
     double g = 0.0;
@@ -631,6 +647,8 @@ int64_t oracle_partition_class_gc(const float *S, int64_t lds, int64_t n, int K,
     }
     if (total_cap > n)
         return -1;
+    if (!is_symmetric(S, lds, n))
+        return -2;
     double *f = (double *)calloc((size_t)K, sizeof(double));
     int64_t *cnt = (int64_t *)calloc((size_t)K, sizeof(int64_t));
     char *open = (char *)malloc((size_t)K);
@@ -709,13 +727,18 @@ int64_t oracle_partition_class_gc(const float *S, int64_t lds, int64_t n, int K,
  * larger magnitude of the two values compared.  A marginal value here is a difference of two
  * sums of similarities, so when the trace was made on a slightly different S (entries off by
  * e each) its values are off by up to n*e however small they are themselves: abs_tol (>= 0,
- * 0 for a trace made on this very S) widens the element window by that absolute amount. */
+ * 0 for a trace made on this very S) widens the element window by that absolute amount: a step
+ * whose sample is not the referee's is accepted when the referee's best marginal value exceeds
+ * the marginal value of the sample taken by at most abs_tol.  Returns -2 for an S that is not
+ * symmetric. */
 int oracle_lockstep_gc(const float *S, int64_t lds, int64_t n, int K, const int64_t *cap,
                        const int32_t *order, const int32_t *assign, int64_t steps,
                        const uint8_t *check, double rel_tol, double abs_tol, int64_t *stats, double *worst)
 {
     if (!S || !cap || !order || !assign || !stats || n < 0 || K < 1 || steps < 0 || steps > n)
         return -1;
+    if (!is_symmetric(S, lds, n))
+        return -2;
     int32_t *elem_at = (int32_t *)malloc((size_t)(steps > 0 ? steps : 1) * sizeof(int32_t));
     int32_t *state = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));   /* block so far, -1 */
     double *f = (double *)calloc((size_t)K, sizeof(double));

@@ -137,3 +137,72 @@ def test_lockstep_referee_accepts_its_own_trace_and_catches_a_planted_swap():
     order[a], order[b] = 40, 10
     assign[a], assign[b] = assign[b], assign[a]
     assert oracle.lockstep(S, cap, order, assign, rel_tol=1e-9, objective="gc")["rc"] == 1
+
+
+def test_absolute_window_of_the_referee_on_a_hand_built_trace():
+    """Three samples, one block of quota 1, dyadic similarities: the marginal values from the empty block are
+    g(0) = 0.5 + 0.25, g(1) = 0.5 + 0.125, g(2) = 0.25 + 0.125 (Section 4's graph-cut f with A = {u}).
+    A trace that takes sample 1 is delta = 0.125 below the best: the referee must accept it exactly when
+    the absolute window reaches delta, and the relative window must stay out of it (rel_tol = 0)."""
+    S = np.array([[1.0, 0.5, 0.25], [0.5, 1.0, 0.125], [0.25, 0.125, 1.0]], dtype=np.float32)
+    assert [f_numpy(S, [u]) for u in range(3)] == [0.75, 0.625, 0.375]
+    cap = [1]
+    order = np.array([-1, 0, -1], dtype=np.int32)
+    assign = np.array([-1, 0, -1], dtype=np.int32)
+    for abs_tol, ok in ((0.125, True), (0.5, True), (0.1249, False), (0.0, False)):
+        res = oracle.lockstep(S, cap, order, assign, rel_tol=0.0, objective="gc", abs_tol=abs_tol)
+        assert (res["rc"] == 0) == ok, (abs_tol, res)
+        assert res["near_elem"] == (1 if ok else 0) and res["violations"] == (0 if ok else 1)
+    # the relative gap reported is delta over the larger magnitude
+    res = oracle.lockstep(S, cap, order, assign, rel_tol=0.0, objective="gc", abs_tol=0.0)
+    assert res["worst_elem_gap"] == 0.125 / 0.75
+    # the best sample itself is exact under a zero window
+    best = oracle.lockstep(S, cap, np.array([0, -1, -1], dtype=np.int32), np.array([0, -1, -1], dtype=np.int32),
+                           rel_tol=0.0, objective="gc", abs_tol=0.0)
+    assert best["rc"] == 0 and best["exact"] == 1
+    # the worst sample is 0.375 below: a window of 0.125 must not let it through
+    worst = oracle.lockstep(S, cap, np.array([-1, -1, 0], dtype=np.int32), np.array([-1, -1, 0], dtype=np.int32),
+                            rel_tol=0.0, objective="gc", abs_tol=0.125)
+    assert worst["rc"] == 1
+
+
+def test_absolute_window_applies_at_a_later_step_with_negative_marginal_values():
+    """Four samples, one block of quota 3, constant similarity c = 0.5 except one pair: at the third step the
+    block holds two samples and the marginal values of the remaining two are (from the definition)
+    g(u) = sum_{v outside, v != u} S(v,u) - sum_{a in A} S(u,a), negative here.  The trace takes the worse one."""
+    S = np.full((4, 4), 0.5, dtype=np.float32)
+    np.fill_diagonal(S, 1.0)
+    S[2, 3] = S[3, 2] = 0.25
+    S[0, 2] = S[2, 0] = 0.75
+    out = oracle.partition_class(S, [3], trace=True, objective="gc")
+    # first two picks from the definition: column sums without the diagonal 1.75, 1.5, 1.5, 1.25 -> sample 0;
+    # then g(1) = 0.5 + 0.5 - 0.5 = 0.5, g(2) = 0.5 + 0.25 - 0.75 = 0, g(3) = 0.5 + 0.25 - 0.5 = 0.25 -> sample 1
+    assert out["tr_elem"][:2].tolist() == [0, 1] and out["tr_gain"][:2].tolist() == [1.75, 0.5]
+    # third step, A = {0, 1}: g(2) = S(3,2) - S(2,0) - S(2,1) = 0.25 - 1.25 = -1.0, g(3) = 0.25 - 1.0 = -0.75
+    base = f_numpy(S, [0, 1])
+    assert f_numpy(S, [0, 1, 2]) - base == -1.0 and f_numpy(S, [0, 1, 3]) - base == -0.75
+    assert out["tr_elem"][2] == 3 and out["tr_gain"][2] == -0.75
+    order = np.array([0, 1, 2, -1], dtype=np.int32)          # the trace takes sample 2 at the third step
+    assign = np.array([0, 0, 0, -1], dtype=np.int32)
+    for abs_tol, ok in ((0.25, True), (0.2499, False)):
+        res = oracle.lockstep(S, [3], order, assign, rel_tol=0.0, objective="gc", abs_tol=abs_tol)
+        assert (res["rc"] == 0) == ok and res["checked"] == 3, (abs_tol, res)
+        assert res["first_violation"] == (-1 if ok else 2)
+
+
+def test_an_asymmetric_similarity_is_evaluated_as_printed_and_refused_by_the_greedy():
+    """Section 4 prints f(A) = sum_{v outside A} sum_{v' in A} sim(v, v'): the first index is the outside
+    sample.  The definition is evaluated that way on any matrix; the greedy and its referee read marginal
+    values along rows, which is only the same thing for a symmetric matrix, and say so by refusing others."""
+    S = np.array([[1.0, 0.5, 0.25], [0.125, 1.0, 0.75], [0.0625, 0.375, 1.0]], dtype=np.float32)
+    # A = {0}: outside samples 1 and 2, terms S[1][0] + S[2][0] (not S[0][1] + S[0][2])
+    assert oracle.f_value(S, [0], "gc") == 0.125 + 0.0625
+    assert oracle.f_value(S, [1, 2], "gc") == 0.5 + 0.25
+    with pytest.raises(ValueError):
+        oracle.partition_class(S, [1, 1], objective="gc")
+    res = oracle.lockstep(S, [1], np.array([0, -1, -1], dtype=np.int32), np.array([0, -1, -1], dtype=np.int32),
+                          rel_tol=1e-5, objective="gc")
+    assert res["rc"] == -2
+    # made symmetric, both run
+    Ssym = np.maximum(S, S.T)
+    assert oracle.partition_class(Ssym, [1, 1], objective="gc")["steps"] == 2
