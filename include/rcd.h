@@ -6,13 +6,25 @@
  * Conventions for every entry point
  *   - `*_dev` arguments are device pointers (HIP global memory on the current
  *     device), `*_host` arguments are host pointers.  The caller owns every
- *     buffer, workspace included; the library keeps no pointer after a call
- *     returns, allocates no device memory and frees nothing.
+ *     buffer, workspace included; the library keeps no pointer to a caller's
+ *     buffer after a call returns, allocates no device memory and frees nothing
+ *     of the caller's.
+ *   - What the library does keep, until rcd_release() or the end of the process:
+ *     per calling thread, one small pinned host buffer (progress records of the
+ *     partition calls), up to four non-blocking streams of its own (the lanes on
+ *     which groups of classes advance side by side) and the events of
+ *     rcd_profile; per device, a record of one-time set-up (kernel attributes,
+ *     the compute-unit count), guarded by a mutex.  Calls from different threads
+ *     are independent as long as their buffers are.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *   - Inputs are never modified.  The return value is an rcd_status; on any
  *     value other than RCD_OK the contents of output buffers are unspecified.
- *     Arguments are validated before the first launch.  No exception or abort
- *     crosses the boundary.
+ *     Everything that can be checked from the arguments is checked before the
+ *     first launch.  The data-set calls learn the class sizes from the class
+ *     split (their first three launches), so the part of their workspace
+ *     requirement that depends on those sizes, a label outside [0, L) and a
+ *     class too large for the mode are reported after the split and before
+ *     anything else runs.  No exception or abort crosses the boundary.
  *   - Same inputs give byte-identical outputs (fixed reduction orders, no
  *     floating-point atomics).
  *   - "lowest index" always means the lowest position in the caller's arrays.
@@ -52,8 +64,10 @@ typedef enum {
                                 taking v* into block k changes cur_k on D = {j : S(j,v*) > cur_k(j)} only, and
                                 gain_k(v) moves by sum_{j in D} [max(0,S(j,v)-new_j) - max(0,S(j,v)-old_j)],
                                 so a step reads |D| rows of S instead of one per candidate.  Same Algorithm 1,
-                                same tie rules; gains are carried in double.  rcd_partition_class takes this
-                                route when the environment variable RCD_INCREMENTAL is 1. */
+                                same tie rules; gains are carried in double, where the sweeps of RCD_MODE_STORED
+                                sum in fp32: the two routes take the same decisions except at steps whose two
+                                best gains differ by less than fp32 rounding of a sum of n terms (inside the
+                                1e-5 relative window either choice is a correct run of Algorithm 1). */
 } rcd_mode;
 
 /*
@@ -134,6 +148,22 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
                         void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /*
+ * rcd_partition_class with the route as an argument (rcd_partition_class itself sweeps a stored S, or
+ * recomputes when S_dev is null):
+ *   RCD_MODE_STORED       S_dev required; one gain sweep over S per round
+ *   RCD_MODE_INCREMENTAL  S_dev required; gains kept current from step to step
+ *   RCD_MODE_RECOMPUTE    X_dev required (S_dev is ignored); S rebuilt tile by tile inside every sweep
+ *   RCD_MODE_AUTO         RCD_MODE_INCREMENTAL if S_dev is non-null, else RCD_MODE_RECOMPUTE
+ * Workspace: rcd_class_workspace_bytes(n, K, mode) (the stored and incremental routes need the same).
+ * Everything else as for rcd_partition_class.
+ */
+int rcd_partition_class_mode(const float *S_dev, int64_t ld_s,
+                             const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
+                             int64_t n, int K, const int64_t *cap_host, int mode,
+                             int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                             void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/*
  * Whole data set (Algorithm 1, outer loop): split the samples by label keeping
  * their order, give every class the quotas of rcd_quota, run the class greedy
  * on every class (classes are advanced together, as many at a time as the
@@ -204,6 +234,24 @@ int rcd_batch_sizes(int64_t B, const int32_t *r_host, int K, int64_t *batch_host
 size_t rcd_class_workspace_bytes(int64_t n, int K, int mode);
 int rcd_dataset_workspace_bytes(int64_t N, int L, int64_t max_class_n, int K, int mode,
                                 size_t *min_bytes, size_t *full_bytes);
+/* One query for both: max_class_n = 0 gives rcd_class_workspace_bytes(N_or_n, K, mode); max_class_n > 0
+ * gives a size with which the data-set calls run N_or_n samples in classes of at most max_class_n
+ * samples whatever the number of classes (one class at a time; rcd_dataset_workspace_bytes, which is
+ * told L, also gives the size that lets all classes advance together).  d and dt do not enter: features
+ * are read in place and S is fp32.  0 on arguments out of range. */
+size_t rcd_workspace_bytes(int64_t N_or_n, int64_t max_class_n, int64_t d, int K, int dt, int mode);
+
+/*
+ * One-time set-up for the current device (kernel attributes, compute-unit count).  Optional: every
+ * entry point does what it needs on its first call; calling this first keeps that work out of a
+ * timed or captured region.
+ */
+int rcd_init(void);
+/*
+ * Frees what the calling thread's earlier calls keep (pinned progress buffer, the library's own
+ * streams, profiling events).  No call of this thread may be in flight.  Later calls set up again.
+ */
+void rcd_release(void);
 
 /* Static description of a status code. */
 const char *rcd_strerror(int status);

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     class_workspace_bytes,
     dataset_workspace_bytes,
     gain_sweep,
+    init,
     last_stats,
     lib_path,
     load_library,
@@ -22,9 +23,11 @@ from .binding import (  # noqa: F401
     profile,
     profile_read,
     quota,
+    release,
     similarity,
     strerror,
     worker_shards,
+    workspace_bytes,
 )
 
 F32 = 0

@@ -18,7 +18,7 @@ EXPORTS = [
     "rcd_partition_class", "rcd_partition_dataset", "rcd_partition_class_graph_cut",
     "rcd_partition_dataset_graph_cut", "rcd_class_workspace_bytes",
     "rcd_dataset_workspace_bytes", "rcd_strerror", "rcd_last_hip_error", "rcd_last_stats",
-    "rcd_profile", "rcd_profile_read",
+    "rcd_profile", "rcd_profile_read", "rcd_partition_class_mode", "rcd_workspace_bytes", "rcd_init", "rcd_release",
 ]
 
 
@@ -85,6 +85,14 @@ def load_library():
     lib.rcd_profile.argtypes = [i32]
     lib.rcd_profile_read.restype = None
     lib.rcd_profile_read.argtypes = [vp]
+    lib.rcd_partition_class_mode.restype = i32
+    lib.rcd_partition_class_mode.argtypes = [vp, i64, vp, i32, i64, i64, f32, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.rcd_workspace_bytes.restype = sz
+    lib.rcd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, i32]
+    lib.rcd_init.restype = i32
+    lib.rcd_init.argtypes = []
+    lib.rcd_release.restype = None
+    lib.rcd_release.argtypes = []
     _lib = lib
     return lib
 
@@ -178,6 +186,19 @@ def dataset_workspace_bytes(N: int, L: int, max_class_n: int, K: int, mode: int 
     return int(mn.value), int(fl.value)
 
 
+def workspace_bytes(N_or_n: int, max_class_n: int, d: int, K: int, dtype_code: int = 0, mode: int = 1) -> int:
+    return int(load_library().rcd_workspace_bytes(int(N_or_n), int(max_class_n), int(d), int(K), int(dtype_code),
+                                                  int(mode)))
+
+
+def init() -> None:
+    _check(load_library().rcd_init())
+
+
+def release() -> None:
+    load_library().rcd_release()
+
+
 def similarity(X, sigma2: float, row_index=None, out=None, workspace=None):
     """X: (n, d) float32/bfloat16 device tensor (row stride = ld_x).  Returns S (n, n) float32."""
     import torch
@@ -229,8 +250,10 @@ def gain_sweep(S, cur, workspace=None):
     return gains
 
 
-def partition_class(S=None, cap=None, X=None, sigma2: float = 1.0, workspace=None, want_order: bool = True):
-    """One class of Algorithm 1.  Give S (stored mode) or X (recompute mode).
+def partition_class(S=None, cap=None, X=None, sigma2: float = 1.0, workspace=None, want_order: bool = True,
+                    mode: Optional[int] = None):
+    """One class of Algorithm 1.  Give S (stored mode) or X (recompute mode).  mode=None calls
+    rcd_partition_class (sweeps over a stored S, or recompute); a mode calls rcd_partition_class_mode.
     Returns (assign int32[n] device, order int32[n] device or None, obj float64[K] numpy)."""
     import torch
 
@@ -243,17 +266,20 @@ def partition_class(S=None, cap=None, X=None, sigma2: float = 1.0, workspace=Non
     assign = torch.empty(n, dtype=torch.int32, device=dev)
     order = torch.empty(n, dtype=torch.int32, device=dev) if want_order else None
     obj = np.zeros(K, dtype=np.float64)
-    mode = 1 if S is not None else 2
     if workspace is None:
-        workspace = _workspace(lib.rcd_class_workspace_bytes(n, K, mode), dev)
+        workspace = _workspace(lib.rcd_class_workspace_bytes(n, K, 1 if S is not None else 2), dev)
     if S is not None:
         assert S.dtype == torch.float32 and S.stride(1) == 1
         args = (_dev_ptr(S), S.stride(0), None, 0, 0, 0, float(sigma2))
     else:
         assert X.stride(1) == 1
         args = (None, 0, _dev_ptr(X), _dtype_code(X), X.shape[1], X.stride(0), float(sigma2))
-    _check(lib.rcd_partition_class(*args, n, K, _np_ptr(cap), _dev_ptr(assign), _dev_ptr(order), _np_ptr(obj),
-                                   _dev_ptr(workspace), workspace.numel(), _stream()))
+    if mode is None:
+        _check(lib.rcd_partition_class(*args, n, K, _np_ptr(cap), _dev_ptr(assign), _dev_ptr(order), _np_ptr(obj),
+                                       _dev_ptr(workspace), workspace.numel(), _stream()))
+    else:
+        _check(lib.rcd_partition_class_mode(*args, n, K, _np_ptr(cap), int(mode), _dev_ptr(assign), _dev_ptr(order),
+                                            _np_ptr(obj), _dev_ptr(workspace), workspace.numel(), _stream()))
     return assign, order, obj
 
 

@@ -16,6 +16,9 @@ HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
     # compiler-generated packed fp32 ops are kept out of every kernel
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # no multiply and add is fused behind the source's back: every fused multiply-add in the kernels is
+    # written as one (fmaf), so an expression gives the same bits in every kernel that evaluates it
+    "-ffp-contract=off",
     "-Wno-unused-value",
 ]
 

@@ -920,6 +920,8 @@ __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsSha
             if (d.order_out) d.order_out[oi] = d.ut[tid];
         }
     }
+    // every wave is done reading cblk[] (the compaction above) before thread 0 rewrites it
+    __syncthreads();
     // ---- the descriptor: what the next sweep must do, the state, the counters
     if (tid == 0) {
         int nneed = 0;
@@ -930,7 +932,7 @@ __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsSha
         if (nneed > 0) {
             // the coverage vectors of the evaluated blocks share the sweep workgroup's LDS:
             // the more blocks, the shorter the chunk of j one pass covers
-            int jc = (RCD_SWEEP_LDS_FLOATS / nneed) / 256 * 256;
+            int jc = rcd_sweep_chunk(nneed);
             jc = jc > ld ? ld : jc;
             const int C = (ld + jc - 1) / jc;
             d.rpc = jc;
@@ -982,6 +984,8 @@ rcd_k_sweep_rows(const RcdClass *__restrict__ classes, const RcdWg *__restrict__
     const RcdClass &st = classes[wg.cls];
     const int nneed = st.nneed;
     if (nneed <= 0 || st.done) return;
+    // the variants are those rcd_sweep_slots() names: all KS slots of a variant are staged, so the
+    // chunk length st.rpc was cut for KS slots, not for nneed
     if (nneed == 1) sweep_rows<1>(st, wg.w, wg.W, lds_cur);
     else if (nneed == 2) sweep_rows<2>(st, wg.w, wg.W, lds_cur);
     else if (nneed == 3) sweep_rows<3>(st, wg.w, wg.W, lds_cur);

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 #include <thread>
 
@@ -19,6 +20,17 @@
 #include "incremental_kernels.hip"
 
 static_assert(RCD_KMAX == RCD_MAX_K, "public and internal block limits differ");
+
+// every sweep variant's staged coverage (slots x chunk of j) stays inside the workgroup's LDS
+constexpr bool sweep_chunks_fit()
+{
+    for (int k = 1; k <= RCD_KMAX; ++k)
+        if (rcd_sweep_slots(k) < k || rcd_sweep_chunk(k) < RCD_TILE ||
+            rcd_sweep_slots(k) * rcd_sweep_chunk(k) > RCD_SWEEP_LDS_FLOATS)
+            return false;
+    return true;
+}
+static_assert(sweep_chunks_fit(), "a stored-S sweep variant would stage past its LDS");
 
 namespace {
 
@@ -88,6 +100,9 @@ size_t class_state_bytes(int64_t n, int K, bool stored)
     return b;
 }
 
+// Most classes a data-set call takes.
+constexpr int RCD_MAX_CLASSES = 8192;
+
 // Classes of a group may be dealt to this many lanes that advance side by side.
 constexpr int RCD_MAX_LANES = 4;
 // Progress records (and their events) a lane cycles through: batches in flight + 1 at most.
@@ -154,8 +169,7 @@ int sweep_items_bound(const RcdClass &c)
 // (the step loop applies the same rule on the device).
 void stored_chunks(int ld, int nneed, int *C, int *jc)
 {
-    int len = (RCD_SWEEP_LDS_FLOATS / std::max(nneed, 1)) / 256 * 256;
-    len = std::min(len, ld);
+    int len = std::min(rcd_sweep_chunk(nneed), ld);
     *jc = len;
     *C = (ld + len - 1) / len;
 }
@@ -191,18 +205,50 @@ std::vector<RcdWg> deal_workgroups(const std::vector<RcdClass> &cls, int total)
     return map;
 }
 
-int g_cu_count = 0;
+// What is set up once per device (kernel attributes are per device): guarded by one mutex, since partition calls may come from several threads.
+constexpr int RCD_MAX_DEVICES = 64;
+struct DeviceSetup {
+    int cus = 0;               // compute units; 0 = sweep kernel not set up yet
+    bool fast_ready = false;   // the matrix-core kernels' LDS limit has been raised
+};
+std::mutex g_setup_mutex;
+DeviceSetup g_dev[RCD_MAX_DEVICES];
+
+// The current device's record, or null (and g_hip_err) if the device cannot be told.
+DeviceSetup *device_setup()
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= RCD_MAX_DEVICES) {
+        snprintf(g_hip_err, sizeof g_hip_err, "hipGetDevice -> %s", e != hipSuccess ? hipGetErrorString(e) : "device index beyond 63");
+        return nullptr;
+    }
+    return &g_dev[dev];
+}
+
 int sweep_setup()
 {
-    if (g_cu_count == 0) {
+    DeviceSetup *ds = device_setup();
+    if (!ds) return RCD_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (ds->cus == 0) {
         int dev = 0, cus = 0;
         HIP_TRY(hipGetDevice(&dev));
         HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rcd_k_sweep_rows),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, RCD_SWEEP_LDS_FLOATS * 4));
-        g_cu_count = std::max(cus, 1);
+        ds->cus = std::max(cus, 1);
     }
     return RCD_OK;
+}
+
+// Compute units of the current device (after sweep_setup() succeeded; 256 if it has not run).
+int cu_count()
+{
+    DeviceSetup *ds = device_setup();
+    if (!ds) return 256;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    return ds->cus > 0 ? ds->cus : 256;
 }
 
 // Fast path of the matrix-core kernels: feature rows that can go straight from global memory
@@ -215,10 +261,12 @@ bool rows_fit_fast_path(const void *X, int dt, int64_t d, int64_t ldx)
 }
 
 // The fast kernels use more LDS than a kernel may by default: raise their limit once.
-bool g_fast_ready = false;
 int fast_setup()
 {
-    if (!g_fast_ready) {
+    DeviceSetup *ds = device_setup();
+    if (!ds) return RCD_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (!ds->fast_ready) {
         const void *sim_kernels[] = {reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float>),
                                      reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<__bf16>),
                                      reinterpret_cast<const void *>(&sim::k_gram_rbf_fast<float, sim::EPI_RBF_MIRROR>),
@@ -240,7 +288,7 @@ int fast_setup()
                                     reinterpret_cast<const void *>(&rcd_k_round_rc_fast<__bf16, false>)};
         for (const void *k : rc_kernels)
             HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, RCD_RC_FAST_LDS));
-        g_fast_ready = true;
+        ds->fast_ready = true;
     }
     return RCD_OK;
 }
@@ -343,7 +391,7 @@ struct Lane {
         HIP_TRY(hipMemcpyAsync(&g->plan_dev[1], &plan0, sizeof plan0, hipMemcpyHostToDevice, stream));
         HIP_TRY(hipMemcpyAsync(g->classes_dev, g->host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
         hipLaunchKernelGGL(rcd_k_init, dim3(64, ncls), dim3(256), 0, stream, g->classes_dev);
-        apply_rc_grid = dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls);
+        apply_rc_grid = dim3((unsigned)((max_n + 127) / 128), (unsigned)ncls);   // a wave takes 32 rows
         // a group is homogeneous: all stored, or all recomputed from the same X
         const RcdClass &first = g->host[0];
         recompute = first.mode == RCD_MODE_RECOMPUTE;
@@ -556,7 +604,7 @@ int run_groups(std::vector<Group> &groups, hipStream_t stream)
     RCD_TRY(sweep_setup());
     // one workgroup of the stored-S sweep fills a compute unit (its LDS holds the coverage vectors);
     // two per unit, run one after the other, even out what the waves of the first leave uneven
-    const int sweep_target = env_int("RCD_SWEEP_WGS", 2 * g_cu_count, 1, RCD_MAX_SWEEP_WGS);
+    const int sweep_target = env_int("RCD_SWEEP_WGS", 2 * cu_count(), 1, RCD_MAX_SWEEP_WGS);
     std::vector<Lane> lanes(nl);
     int rc = RCD_OK;
     int started = 0;
@@ -638,7 +686,7 @@ bool mirror_wanted(int dt, int64_t d, int64_t tiles_in_flight)
 {
     const int mode = env_int("RCD_SIM_MIRROR", 1, 0, 2);
     if (mode != 1) return mode == 2;
-    return (dt == RCD_F32 ? 32 : 2) * d >= 2048 && sweep_setup() == RCD_OK && tiles_in_flight > g_cu_count;
+    return (dt == RCD_F32 ? 32 : 2) * d >= 2048 && sweep_setup() == RCD_OK && tiles_in_flight > cu_count();
 }
 
 int launch_similarity(const void *X, int dt, int64_t n, int64_t d, int64_t ldx, const int32_t *row_index,
@@ -1079,6 +1127,44 @@ int rcd_dataset_workspace_bytes(int64_t N, int L, int64_t max_class_n, int K, in
     return RCD_OK;
 }
 
+size_t rcd_workspace_bytes(int64_t N_or_n, int64_t max_class_n, int64_t d, int K, int dt, int mode)
+{
+    (void)d;    // features are read in place and S is fp32 whatever the feature type:
+    (void)dt;   // neither enters the size
+    if (N_or_n <= 0 || K < 1 || K > RCD_MAX_K || max_class_n < 0 || max_class_n > N_or_n) return 0;
+    if (max_class_n == 0) return rcd_class_workspace_bytes(N_or_n, K, mode);
+    // a data set: the smallest size that works whatever the number of classes
+    const int L = (int)std::min<int64_t>(N_or_n, RCD_MAX_CLASSES);
+    size_t mn = 0;
+    if (rcd_dataset_workspace_bytes(N_or_n, L, max_class_n, K, mode, &mn, nullptr) != RCD_OK) return 0;
+    return mn;
+}
+
+int rcd_init(void)
+{
+    RCD_TRY(sweep_setup());
+    RCD_TRY(fast_setup());
+    return RCD_OK;
+}
+
+void rcd_release(void)
+{
+    for (int i = 0; i < RCD_MAX_LANES; ++i)
+        if (g_side[i]) {
+            (void)hipStreamSynchronize(g_side[i]);
+            (void)hipStreamDestroy(g_side[i]);
+            g_side[i] = nullptr;
+        }
+    for (int i = 0; i < 4; ++i) {
+        for (hipEvent_t e : g_prof_ev[i]) (void)hipEventDestroy(e);
+        g_prof_ev[i].clear();
+    }
+    if (g_pinned) {
+        (void)hipHostFree(g_pinned);
+        g_pinned = nullptr;
+    }
+}
+
 int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const float *cur_dev,
                    float *gains_dev, void *workspace_dev, size_t workspace_bytes, void *stream_)
 {
@@ -1101,7 +1187,7 @@ int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const flo
     stored_chunks(c.ld, K, &c.C, &c.rpc);
     RCD_TRY(sweep_setup());
     const std::vector<RcdWg> map =
-        deal_workgroups(g.host, env_int("RCD_SWEEP_WGS", 2 * g_cu_count, 1, RCD_MAX_SWEEP_WGS));
+        deal_workgroups(g.host, env_int("RCD_SWEEP_WGS", 2 * cu_count(), 1, RCD_MAX_SWEEP_WGS));
     RcdPlan plan[2];
     memset(plan, 0, sizeof plan);
     plan[0].ncls = plan[1].ncls = 1;
@@ -1126,7 +1212,8 @@ int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const flo
 }
 
 // objective: 0 = facility location, 1 = graph cut (stored S only)
-static int partition_class_impl(int objective, const float *S_dev, int64_t ld_s,
+// incremental: stored S, facility location: gains kept current by update lists instead of sweeps
+static int partition_class_impl(int objective, bool incremental, const float *S_dev, int64_t ld_s,
                                 const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
                                 int64_t n, int K, const int64_t *cap_host,
                                 int32_t *assign_dev, int32_t *order_dev, double *obj_host,
@@ -1166,7 +1253,7 @@ static int partition_class_impl(int objective, const float *S_dev, int64_t ld_s,
     c.assign_out = assign_dev;
     c.order_out = order_dev;
     c.objective = objective;
-    c.incremental = stored && objective == 0 && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0;
+    c.incremental = stored && objective == 0 && incremental;
     if (c.incremental)
         for (int k = 0; k < K; ++k) c.valid[k] = 1;      // the initial gains (column sums) are current
     HIP_TRY(hipMemsetAsync(g.plan_dev, 0, 2 * sizeof(RcdPlan), stream));
@@ -1188,8 +1275,33 @@ int rcd_partition_class(const float *S_dev, int64_t ld_s,
                         int32_t *assign_dev, int32_t *order_dev, double *obj_host,
                         void *workspace_dev, size_t workspace_bytes, void *stream)
 {
-    return partition_class_impl(0, S_dev, ld_s, X_dev, dt, d, ld_x, sigma2, n, K, cap_host, assign_dev, order_dev,
-                                obj_host, workspace_dev, workspace_bytes, stream);
+    return partition_class_impl(0, false, S_dev, ld_s, X_dev, dt, d, ld_x, sigma2, n, K, cap_host, assign_dev,
+                                order_dev, obj_host, workspace_dev, workspace_bytes, stream);
+}
+
+int rcd_partition_class_mode(const float *S_dev, int64_t ld_s,
+                             const void *X_dev, int dt, int64_t d, int64_t ld_x, float sigma2,
+                             int64_t n, int K, const int64_t *cap_host, int mode,
+                             int32_t *assign_dev, int32_t *order_dev, double *obj_host,
+                             void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    switch (mode) {
+    case RCD_MODE_AUTO:
+        // like the data-set call: gains kept current whenever S is stored
+        return partition_class_impl(0, S_dev != nullptr, S_dev, ld_s, X_dev, dt, d, ld_x, sigma2, n, K, cap_host,
+                                    assign_dev, order_dev, obj_host, workspace_dev, workspace_bytes, stream);
+    case RCD_MODE_STORED:
+    case RCD_MODE_INCREMENTAL:
+        if (!S_dev && n > 0) return RCD_ERR_INVALID_ARG;
+        return partition_class_impl(0, mode == RCD_MODE_INCREMENTAL, S_dev, ld_s, nullptr, RCD_F32, 0, 0, 0.f, n, K,
+                                    cap_host, assign_dev, order_dev, obj_host, workspace_dev, workspace_bytes, stream);
+    case RCD_MODE_RECOMPUTE:
+        if (!X_dev && n > 0) return RCD_ERR_INVALID_ARG;
+        return partition_class_impl(0, false, nullptr, 0, X_dev, dt, d, ld_x, sigma2, n, K, cap_host, assign_dev,
+                                    order_dev, obj_host, workspace_dev, workspace_bytes, stream);
+    default:
+        return RCD_ERR_UNSUPPORTED;
+    }
 }
 
 int rcd_partition_class_graph_cut(const float *S_dev, int64_t ld_s, int64_t n, int K, const int64_t *cap_host,
@@ -1197,8 +1309,8 @@ int rcd_partition_class_graph_cut(const float *S_dev, int64_t ld_s, int64_t n, i
                                   void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     if (!S_dev && n > 0) return RCD_ERR_INVALID_ARG;
-    return partition_class_impl(1, S_dev, ld_s, nullptr, RCD_F32, 0, 0, 0.f, n, K, cap_host, assign_dev, order_dev,
-                                obj_host, workspace_dev, workspace_bytes, stream);
+    return partition_class_impl(1, false, S_dev, ld_s, nullptr, RCD_F32, 0, 0, 0.f, n, K, cap_host, assign_dev,
+                                order_dev, obj_host, workspace_dev, workspace_bytes, stream);
 }
 
 static int partition_dataset_impl(int objective, const void *X_dev, int dt, int64_t N, int64_t d, int64_t ld_x,
@@ -1211,12 +1323,11 @@ static int partition_dataset_impl(int objective, const void *X_dev, int dt, int6
     reset_stats();
     RCD_TRY(check_common(N, K));
     if (L < 1 || !r_host || !obj_host) return RCD_ERR_INVALID_ARG;
-    if (L > 8192) return RCD_ERR_UNSUPPORTED;
+    if (L > RCD_MAX_CLASSES) return RCD_ERR_UNSUPPORTED;
     if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
     if (mode != RCD_MODE_AUTO && mode != RCD_MODE_STORED && mode != RCD_MODE_RECOMPUTE && mode != RCD_MODE_INCREMENTAL)
         return RCD_ERR_UNSUPPORTED;
-    const bool incremental = objective == 0 && (mode == RCD_MODE_INCREMENTAL ||
-                                                (mode != RCD_MODE_RECOMPUTE && env_int("RCD_INCREMENTAL", 0, 0, 1) != 0));
+    const bool incremental = objective == 0 && mode == RCD_MODE_INCREMENTAL;
     if (d < 1 || ld_x < d || !(sigma2 > 0.f) || !std::isfinite(sigma2)) return RCD_ERR_INVALID_ARG;
     for (int k = 0; k < K; ++k)
         if (r_host[k] < 1) return RCD_ERR_BAD_CAPACITY;

@@ -3,8 +3,9 @@
 // advanced; all classes of a group move in lock step, one "round" at a time:
 //   sweep  - recomputes the gain rows that went stale
 //   steps  - runs as many greedy steps as the current gain rows allow
-// Both happen inside one launch per round (see rcd_k_round).
+// A round is one sweep launch and one step-loop launch (recompute mode can fuse the two: rcd_k_round_rc_fast).
 #pragma once
+#include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #define RCD_KMAX 16          // must equal RCD_MAX_K of the public header
@@ -17,6 +18,19 @@
 #define RCD_SWEEP_THREADS (64 * RCD_SWEEP_WAVES)
 #define RCD_SWEEP_LDS_FLOATS 32768   // LDS of a stored-S sweep workgroup: coverage of the evaluated blocks, one chunk of j
 #define RCD_STEP_THREADS 1024
+
+// The stored-S sweep kernel exists for these numbers of evaluated blocks; a sweep of nneed blocks runs
+// the smallest variant that holds them and stages that many coverage vectors (the spare slots repeat the
+// last block), so the chunk of j one pass covers is cut for the variant's slots: slots x chunk floats
+// never exceed the workgroup's LDS.
+__host__ __device__ constexpr int rcd_sweep_slots(int nneed)
+{
+    return nneed <= 1 ? 1 : nneed <= 4 ? nneed : nneed <= 6 ? 6 : nneed <= 8 ? 8 : nneed <= 12 ? 12 : 16;
+}
+__host__ __device__ constexpr int rcd_sweep_chunk(int nneed)
+{
+    return (RCD_SWEEP_LDS_FLOATS / rcd_sweep_slots(nneed)) / 256 * 256;
+}
 
 struct RcdClass {
     // ---- fixed for the run

@@ -394,36 +394,78 @@ rcd_k_round_rc_fast(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans,
 }
 
 // Apply kernel of the recompute mode: there is no stored matrix, so the coverage
-// update cur_js(j) = max(cur_js(j), S(j, v*)) recomputes the one similarity column
-// it needs from the features: one wave per row j, fp32 accumulation, same
-// clamp / exp2 arithmetic as the sweep's epilogue.  Row block 0 also moves the
-// gains and perm entries and writes the caller's arrays.
+// update cur_js(j) = max(cur_js(j), S(j, v*)) rebuilds the similarity columns it needs
+// from the features.  The sweep that follows subtracts these coverage values from tiles
+// that the matrix cores produce, so the columns come from the matrix cores too, with the
+// same products in the same order: k advances in 32-byte groups, lanes 0-31 of a group
+// carry its first 16 bytes and lanes 32-63 the second, one 32x32x16 multiply per group
+// (bf16) or four 32x32x2 ones (fp32), one accumulator per element, then the epilogue
+// expression every similarity goes through.  An element of a matrix-core product depends
+// only on its own row of each operand, so S(j, v*) here is the S(j, v*) of the sweep's
+// tiles and of the similarity build, bit for bit (tested).
+// One wave = 32 rows j x the samples taken this round (at most 16, one per block; the
+// other columns of the 32 repeat the first and are dropped).  grid = (ceil(n / 128), classes).
+// Row block 0 also moves the gains and perm entries and writes the caller's arrays.
 template <typename T>
 __global__ void __launch_bounds__(256)
 rcd_k_apply_rc(RcdClass *__restrict__ classes, int round_no)
 {
+    using namespace sim;
     RcdClass &st = classes[blockIdx.y];
     if (st.apply_round != round_no) return;
     const int nupd = st.nupd, npatch = st.npatch;
     const int n = st.n, ld = st.ld, K = st.K, d = st.d;
     const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const T *X = reinterpret_cast<const T *>(st.X);
-    if (j < n) {
-        const T *xj = X + (size_t)(st.x_index ? st.x_index[j] : j) * st.ldx64;
-        for (int i = 0; i < nupd; ++i) {
-            const int v = st.uv[i];
-            const T *xv = X + (size_t)(st.x_index ? st.x_index[v] : v) * st.ldx64;
-            float dot = 0.f;
-            for (int t = lane; t < d; t += 64) dot = fmaf(sim::to_f32(xj[t]), sim::to_f32(xv[t]), dot);
+    const int jbase = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 32;
+    if (jbase < n && nupd > 0) {
+        const T *X = reinterpret_cast<const T *>(st.X);
+        const long long ldx = st.ldx64;
+        const bool vec_ok = (reinterpret_cast<uintptr_t>(st.X) & 15) == 0 && ((ldx * (long long)sizeof(T)) % 16) == 0;
+        constexpr int EPC = CHUNK / (int)sizeof(T);      // elements in 16 bytes
+        const int col = lane & 31;
+        const int u = col < nupd ? col : 0;
+        const int v = st.uv[u];
+        const int jrow = min(jbase + col, n - 1);
+        const int ra = st.x_index ? st.x_index[jrow] : jrow;   // x_i operand: row j
+        const int rb = st.x_index ? st.x_index[v] : v;         // x_j operand: the taken sample
+        const int half = (lane >> 5) * EPC;
+        f32x16 acc;
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
-            if (lane == 0) {
-                const float s = (j == v) ? 1.f
-                                         : sim::rbf_value(dot, st.sq[j] * st.exp_scale, st.sq[v] * st.exp_scale,
-                                                          -2.f * st.exp_scale);
-                float *c = st.cur + (size_t)st.ujs[i] * ld + j;
-                if (s > *c) *c = s;
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        // four 32-byte groups of k per trip (groups past d are zeros and add nothing)
+        for (int k0 = 0; k0 < d; k0 += 8 * EPC) {
+            uint4 fa[4], fb[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                fa[g] = load_chunk<T>(X, ldx, ra, k0 + g * 2 * EPC + half, d, vec_ok);
+                fb[g] = load_chunk<T>(X, ldx, rb, k0 + g * 2 * EPC + half, d, vec_ok);
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if constexpr (sizeof(T) == 2) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[g]),
+                                                                  __builtin_bit_cast(bf16x8, fb[g]), acc, 0, 0, 0);
+                } else {
+                    const f32x4 va = __builtin_bit_cast(f32x4, fa[g]);
+                    const f32x4 vb = __builtin_bit_cast(f32x4, fb[g]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], vb[e], acc, 0, 0, 0);
+                }
+            }
+        }
+        // a lane holds column `col`, rows jbase + 8 (r / 4) + 4 (lane >> 5) + (r & 3)
+        if (col < nupd) {
+            const float exp_scale = st.exp_scale;
+            const float scale2 = -2.f * exp_scale;
+            const float sqv = st.sq[v] * exp_scale;
+            float *cur = st.cur + (size_t)st.ujs[col] * ld;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = jbase + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (j < n) {
+                    const float s = (j == v) ? 1.f : rbf_value(acc[r], st.sq[j] * exp_scale, sqv, scale2);
+                    if (s > cur[j]) cur[j] = s;
+                }
             }
         }
     }

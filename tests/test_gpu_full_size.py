@@ -49,6 +49,41 @@ def run_full(rcd, ds, mode):
     return Xd, assign.cpu().numpy(), order.cpu().numpy(), obj
 
 
+def referee_classes(rcd, ds, Xd, assign, order, obj, rng, n_steps, sim_tol, classes):
+    """check_class on several classes with the oracle's referees running side by side: the similarity
+    matrices are fetched from the GPU one after the other, the (single-threaded, GIL-free) oracle calls of
+    different classes run on a small thread pool.  Returns the referee's report per class."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    K = len(ds.r)
+    jobs = []
+    for c in classes:
+        idx = np.flatnonzero(ds.labels == c)
+        n = len(idx)
+        cap = oracle.quota(n, ds.r)
+        a, o = assign[idx], order[idx]
+        assert np.bincount(a, minlength=K).tolist() == cap.tolist()
+        assert np.array_equal(np.sort(o), np.arange(n))
+        S = rcd.similarity(Xd, ds.sigma2, row_index=dev(idx.astype(np.int32))).cpu().numpy()
+        sub = np.sort(rng.choice(n, size=min(192, n), replace=False))
+        steps = sampled_steps(n, rng, n_steps)
+        jobs.append((c, idx, cap, a, o, S, sub, steps))
+
+    def one(job):
+        c, idx, cap, a, o, S, sub, steps = job
+        ref = oracle.similarity(ds.X[idx[sub]], ds.sigma2)
+        assert np.max(np.abs(S[np.ix_(sub, sub)] - ref) / ref) <= sim_tol, c
+        res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, check=steps)
+        assert res["rc"] == 0 and res["checked"] == len(steps), (c, res)
+        for k in range(K):
+            ref_f = oracle.f_value(S, np.flatnonzero(a == k))
+            assert abs(obj[c, k] - ref_f) <= 1e-4 * ref_f, (c, k)
+        return c, res
+
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        return dict(pool.map(one, jobs))
+
+
 def check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps, sim_tol, referee=True):
     idx = np.flatnonzero(ds.labels == c)
     n = len(idx)
@@ -85,14 +120,13 @@ def test_full_size_stored_workloads(rcd, name):
     stats = rcd.last_stats()
     assert stats["steps"] == ds.X.shape[0]
     rng = np.random.default_rng(11)
-    near = 0
-    for c in range(ds.L):
-        # every class: invariants; three classes: similarity samples, referee, objectives
-        res = check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=14, sim_tol=1e-5, referee=c in (0, 4, 9))
-        if res:
-            near += res["near_block"] + res["near_elem"]
-        print(f"  class {c} ok", flush=True)
-    print(f"  sampled near-ties accepted: {near}; stats {stats}", flush=True)
+    # every class: invariants, similarity samples, objectives from the definition, and the referee at the
+    # first, middle and last steps plus 100 steps drawn at random (about 105 of the class's 5000)
+    reports = referee_classes(rcd, ds, Xd, assign, order, obj, rng, n_steps=100, sim_tol=1e-5, classes=range(ds.L))
+    near = sum(r["near_block"] + r["near_elem"] for r in reports.values())
+    assert len(reports) == ds.L and all(r["checked"] >= 100 for r in reports.values())
+    print(f"  steps refereed: {sum(r['checked'] for r in reports.values())}, near-ties accepted: {near}; stats {stats}",
+          flush=True)
     # identical class balance in every class
     per_class = [np.bincount(assign[ds.labels == c], minlength=len(ds.r)) for c in range(ds.L)]
     assert all(np.array_equal(p, per_class[0]) for p in per_class)
@@ -152,6 +186,14 @@ def test_large_class_full_size_window_recompute_equals_stored(rcd):
     cols = S[:, torch.from_numpy(members).cuda()].max(dim=1).values.double().sum().item()
     assert abs(f1[0] - cols) <= 1e-4 * cols
     print(f"  stats {s1}", flush=True)
+    # the oracle referees steps of the recompute route's own trace at this size (first, middle, last of the
+    # window), on the stored matrix the route never saw: 50 000 candidates x 50 000 terms per refereed step
+    Sh = S.cpu().numpy()
+    del S
+    steps = [0, 1, 7, 8, 23, 24, 46, 47]
+    res = oracle.lockstep(Sh, cap, o1, a1, rel_tol=1e-5, check=steps)
+    print(f"  referee on the recompute trace: {res}", flush=True)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
 
 
 # ------------------------------------------------------------------ incremental-gain route at full size
@@ -163,12 +205,24 @@ def test_full_size_incremental_workloads(rcd, name):
     stats = rcd.last_stats()
     assert stats["steps"] == ds.X.shape[0]
     rng = np.random.default_rng(21)
-    for c in range(ds.L):
-        check_class(rcd, ds, Xd, c, assign, order, obj, rng, n_steps=14, sim_tol=1e-5, referee=c in (1, 5, 8))
-    print(f"  stats {stats}", flush=True)
-    # the sweep route on the same data takes the same decisions (up to near-ties, which show in the objectives)
+    reports = referee_classes(rcd, ds, Xd, assign, order, obj, rng, n_steps=100, sim_tol=1e-5, classes=range(ds.L))
+    assert len(reports) == ds.L and all(r["checked"] >= 100 for r in reports.values())
+    print(f"  steps refereed: {sum(r['checked'] for r in reports.values())}; stats {stats}", flush=True)
+    # The sweep route on the same data: the two routes' contract is the same decisions except at steps whose two
+    # best gains differ by less than fp32 rounding (this route carries gains in double, the sweeps sum in fp32).
+    # A class whose traces differ must differ first at such a step, as the oracle sees it.
     _, a2, o2, f2 = run_full(rcd, ds, rcd.MODE_STORED)
     print("  agreement with the sweep route:", np.mean(assign == a2), flush=True)
+    for c in range(ds.L):
+        idx = np.flatnonzero(ds.labels == c)
+        if np.array_equal(assign[idx], a2[idx]) and np.array_equal(order[idx], o2[idx]):
+            continue
+        differ = (assign[idx] != a2[idx]) | (order[idx] != o2[idx])
+        first = int(min(order[idx][differ].min(), o2[idx][differ].min()))
+        S = rcd.similarity(Xd, ds.sigma2, row_index=dev(idx.astype(np.int32))).cpu().numpy()
+        at = oracle.lockstep(S, oracle.quota(len(idx), ds.r), o2[idx], a2[idx], rel_tol=0.0, check=[first])
+        print(f"  class {c}: traces part at step {first}: {at}", flush=True)
+        assert at["worst_elem_gap"] <= 1e-5 and at["worst_block_gap"] <= 1e-5, (c, first, at)
     assert np.allclose(obj, f2, rtol=1e-4)
 
 
@@ -194,16 +248,7 @@ def test_large_class_one_full_class_incremental(rcd):
     S = rcd.similarity(Xd, float(w.d))
     cap = oracle.quota(w.n_c, w.r)
     assert cap.tolist() == [2083, 2083, 4166, 4166, 6251, 6250, 8334, 16667]
-    import os
-    old = os.environ.get("RCD_INCREMENTAL")
-    os.environ["RCD_INCREMENTAL"] = "1"
-    try:
-        a, o, f = rcd.partition_class(S=S, cap=cap)
-    finally:
-        if old is None:
-            del os.environ["RCD_INCREMENTAL"]
-        else:
-            os.environ["RCD_INCREMENTAL"] = old
+    a, o, f = rcd.partition_class(S=S, cap=cap, mode=rcd.MODE_INCREMENTAL)
     stats = rcd.last_stats()
     print(f"  stats {stats}", flush=True)
     a, o = a.cpu().numpy(), o.cpu().numpy()
@@ -392,19 +437,11 @@ def test_sixteen_blocks_on_a_12000_sample_class(rcd, route):
     X = si.make_class(seed=91, n=n, d=d, G=8)
     S = rcd.similarity(dev(X), float(d))
     cap = oracle.quota(n, r)
-    import os
-    old = os.environ.get("RCD_INCREMENTAL")
-    os.environ["RCD_INCREMENTAL"] = "1" if route == "incremental" else "0"
-    try:
-        if route == "graph_cut":
-            a, o, f = rcd.partition_class_graph_cut(S, cap)
-        else:
-            a, o, f = rcd.partition_class(S=S, cap=cap)
-    finally:
-        if old is None:
-            del os.environ["RCD_INCREMENTAL"]
-        else:
-            os.environ["RCD_INCREMENTAL"] = old
+    if route == "graph_cut":
+        a, o, f = rcd.partition_class_graph_cut(S, cap)
+    else:
+        a, o, f = rcd.partition_class(S=S, cap=cap,
+                                      mode=rcd.MODE_INCREMENTAL if route == "incremental" else rcd.MODE_STORED)
     a, o = a.cpu().numpy(), o.cpu().numpy()
     assert np.bincount(a, minlength=16).tolist() == cap.tolist()
     assert np.array_equal(np.sort(o), np.arange(n))

@@ -1,4 +1,4 @@
-"""GPU parity of the incremental-gain route (RCD_MODE_INCREMENTAL / RCD_INCREMENTAL=1): the same
+"""GPU parity of the incremental-gain route (RCD_MODE_INCREMENTAL through rcd_partition_class_mode): the same
 Algorithm 1, with every block's gains kept current from step to step instead of rebuilt by
 sweeps.  Checked like the sweep route: the oracle's lock-step referee on the same S, exact-tie
 cases with a zero window, objectives from the definition, quota and cover invariants; and the
@@ -34,9 +34,9 @@ def mixture_S(seed, n, d=16):
     return oracle.similarity(si.make_class(seed=seed, n=n, d=d), float(d))
 
 
-def run_class(rcd, S, cap, monkeypatch, incremental=True):
-    monkeypatch.setenv("RCD_INCREMENTAL", "1" if incremental else "0")
-    assign, order, obj = rcd.partition_class(S=dev(S), cap=cap)
+def run_class(rcd, S, cap, incremental=True):
+    assign, order, obj = rcd.partition_class(S=dev(S), cap=cap,
+                                             mode=rcd.MODE_INCREMENTAL if incremental else rcd.MODE_STORED)
     return assign.cpu().numpy(), order.cpu().numpy(), obj
 
 
@@ -57,11 +57,11 @@ def check_against_oracle(S, cap, assign, order, obj, exact=False):
 
 @pytest.mark.parametrize("n,r", [(1, [1]), (250, [1, 1]), (600, [1, 1, 2, 4]), (1000, [1, 1, 1, 2, 2, 3, 4, 6]),
                                  (520, [3, 1, 4, 1, 2, 2, 1, 3, 4, 4, 1, 2, 3, 3, 2, 1]), (257, [5]), (1300, [2, 1])])
-def test_incremental_class_greedy_lockstep(rcd, monkeypatch, n, r):
+def test_incremental_class_greedy_lockstep(rcd, n, r):
     print(f"incremental class greedy n={n} K={len(r)}", flush=True)
     S = mixture_S(400 + n, n)
     cap = oracle.quota(n, r)
-    assign, order, obj = run_class(rcd, S, cap, monkeypatch)
+    assign, order, obj = run_class(rcd, S, cap)
     res = check_against_oracle(S, cap, assign, order, obj)
     stats = rcd.last_stats()
     assert stats["steps"] == n
@@ -76,27 +76,27 @@ def test_incremental_class_greedy_lockstep(rcd, monkeypatch, n, r):
         assert stats["entries_streamed"] < n * n * (n + 1) // 2
 
 
-def test_incremental_exact_ties_follow_the_lowest_index_contract(rcd, monkeypatch):
+def test_incremental_exact_ties_follow_the_lowest_index_contract(rcd):
     # constant similarity: every gain ties exactly
     n, c = 96, 0.25
     S = np.full((n, n), c, dtype=np.float32)
     np.fill_diagonal(S, 1.0)
     for cap in ([32, 32, 32], [10, 30, 56], [96]):
-        assign, order, obj = run_class(rcd, S, cap, monkeypatch)
+        assign, order, obj = run_class(rcd, S, cap)
         ref = oracle.partition_class(S, cap)
         assert np.array_equal(assign, ref["assign"]) and np.array_equal(order, ref["order"])
         assert obj.tolist() == [m + (n - m) * c for m in cap]
         check_against_oracle(S, cap, assign, order, obj, exact=True)
 
 
-def test_incremental_duplicate_samples_tie_exactly(rcd, monkeypatch):
+def test_incremental_duplicate_samples_tie_exactly(rcd):
     # every sample appears twice: the copies' gains must stay equal bit for bit through all the
     # updates, so that the lower index of a pair is always the one taken first
     base = si.make_class(seed=31, n=150, d=16)
     X = np.concatenate([base, base], axis=0)
     S = oracle.similarity(X, 16.0)
     cap = oracle.quota(300, [1, 2])
-    assign, order, obj = run_class(rcd, S, cap, monkeypatch)
+    assign, order, obj = run_class(rcd, S, cap)
     check_against_oracle(S, cap, assign, order, obj, exact=False)
     ref = oracle.partition_class(S, cap)
     # whenever both copies of a sample go to the same block, the first copy goes first
@@ -106,25 +106,34 @@ def test_incremental_duplicate_samples_tie_exactly(rcd, monkeypatch):
     assert np.allclose(obj, ref["obj"], rtol=1e-4)
 
 
-def test_incremental_zero_quota_and_leftovers(rcd, monkeypatch):
+def test_incremental_zero_quota_and_leftovers(rcd):
     S = mixture_S(18, 300)
     cap = [0, 40, 0, 25]
-    assign, order, obj = run_class(rcd, S, cap, monkeypatch)
+    assign, order, obj = run_class(rcd, S, cap)
     check_against_oracle(S, cap, assign, order, obj)
     assert obj[0] == 0.0 and obj[2] == 0.0
     assert np.sum(assign == -1) == 235 and np.all(order[assign == -1] == -1)
-    assign, order, obj = run_class(rcd, S, [0, 0], monkeypatch)
+    assign, order, obj = run_class(rcd, S, [0, 0])
     assert np.all(assign == -1) and np.all(obj == 0.0)
 
 
-def test_incremental_agrees_with_the_sweep_route_and_is_deterministic(rcd, monkeypatch):
+def test_incremental_agrees_with_the_sweep_route_and_is_deterministic(rcd):
     S = mixture_S(19, 700)
     cap = oracle.quota(700, [1, 2, 3])
-    a1, o1, f1 = run_class(rcd, S, cap, monkeypatch)
-    a2, o2, f2 = run_class(rcd, S, cap, monkeypatch)
+    a1, o1, f1 = run_class(rcd, S, cap)
+    a2, o2, f2 = run_class(rcd, S, cap)
     assert np.array_equal(a1, a2) and np.array_equal(o1, o2) and np.array_equal(f1, f2)
-    a3, o3, f3 = run_class(rcd, S, cap, monkeypatch, incremental=False)
+    a3, o3, f3 = run_class(rcd, S, cap, incremental=False)
+    # the two routes' contract: the same decisions except at steps whose two best gains differ by less than
+    # fp32 rounding; each route's trace is a correct run of Algorithm 1 under the 1e-5 window
     print("  incremental vs sweep agreement:", np.mean(a1 == a3), flush=True)
+    if not np.array_equal(a1, a3):
+        first = int(min(o1[a1 != a3].min(), o3[a1 != a3].min()))
+        at = oracle.lockstep(S, cap, o3, a3, rel_tol=0.0, check=[first])
+        assert at["worst_elem_gap"] <= 1e-5 and at["worst_block_gap"] <= 1e-5, (first, at)
+    for a, o in ((a1, o1), (a3, o3)):
+        res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5)
+        assert res["rc"] == 0 and res["checked"] == cap.sum(), res
     assert np.allclose(f1, f3, rtol=1e-4)
 
 

@@ -291,11 +291,38 @@ def test_class_greedy_recompute_mode(rcd, dtype, n, d, r):
     S_gpu = rcd.similarity(dev(X), float(d)).cpu().numpy()
     assert rel_err(S_gpu, S_ref) <= (1e-5 if dtype == "f32" else 2e-2)
     check_against_oracle(S_gpu, cap, assign, order, obj)
-    # the stored-S path on the same class takes the same decisions
+    # the stored-S path on the same class takes the same decisions: both routes work on the same bits of S
+    # (the sweep's tiles and the coverage update's columns are those of the stored matrix); their gain sums
+    # differ only in fp32 summation order, so a differing step can only be a near-tie of that size
     a2, o2, f2 = rcd.partition_class(S=dev(S_gpu), cap=cap)
-    same = np.mean(a2.cpu().numpy() == assign)
+    a2, o2 = a2.cpu().numpy(), o2.cpu().numpy()
+    same = np.mean(a2 == assign)
     print("  recompute vs stored agreement:", same, flush=True)
+    if not np.array_equal(a2, assign):
+        first = int(min(order[a2 != assign].min(), o2[a2 != assign].min()))
+        at = oracle.lockstep(S_gpu, cap, o2, a2, rel_tol=0.0, check=[first])
+        print("  first differing step", first, at, flush=True)
+        assert at["worst_elem_gap"] <= 2e-6 and at["worst_block_gap"] <= 2e-6, (first, at)
     assert np.allclose(f2, obj, rtol=1e-4)
+
+
+@pytest.mark.parametrize("dtype,n,d", [("bf16", 700, 256), ("f32", 515, 64), ("bf16", 300, 40), ("f32", 130, 24),
+                                       ("bf16", 1100, 2048), ("f32", 333, 512)])
+def test_recompute_route_works_on_the_bits_of_the_stored_similarity(rcd, dtype, n, d):
+    """Greedy with every quota 1 on K = n' <= 16 blocks: after the first round each block holds one sample, so
+    its coverage vector is one column of S as the recompute route's coverage update rebuilt it.  The final
+    objective of block k is then the column sum of S(., v_k) in double, which must equal, to the last bit,
+    the same sum over the matrix rcd_similarity stores (both Gram paths, aligned and ragged d)."""
+    print(f"recompute columns vs stored similarity {dtype} n={n} d={d}", flush=True)
+    X = si.make_class(seed=900 + n, n=n, d=d, G=8, dtype=dtype)
+    K = 16
+    cap = np.ones(K, dtype=np.int64)
+    a, o, f = rcd.partition_class(X=dev(X), cap=cap, sigma2=float(d))
+    a = a.cpu().numpy()
+    S_gpu = rcd.similarity(dev(X), float(d)).cpu().numpy()
+    for k in range(K):
+        v = int(np.flatnonzero(a == k)[0])
+        assert f[k] == float(S_gpu[:, v].astype(np.float64).sum()), (k, v)
 
 
 @pytest.mark.parametrize("dtype,n,d,r", [("f32", 600, 32, [1] * 16), ("bf16", 1000, 64, [3, 1, 2]),

@@ -43,7 +43,7 @@ def random_case(seed):
 
 
 @pytest.mark.parametrize("seed", range(24))
-def test_random_class_on_every_route(rcd, monkeypatch, seed):
+def test_random_class_on_every_route(rcd, seed):
     X, cap, sigma2, repeated = random_case(1000 + seed)
     n, K = X.shape[0], len(cap)
     print(f"random case {seed}: n={n} K={K} d={X.shape[1]} sum of quotas {int(cap.sum())}", flush=True)
@@ -51,24 +51,19 @@ def test_random_class_on_every_route(rcd, monkeypatch, seed):
     Sd = rcd.similarity(Xd, sigma2)
     S = Sd.cpu().numpy()
     assert np.max(np.abs(S - oracle.similarity(X, sigma2)) / np.maximum(oracle.similarity(X, sigma2), 1e-30)) <= 1e-5
-    routes = [("sweeps", "fl", lambda: rcd.partition_class(S=Sd, cap=cap)),
-              ("incremental", "fl", lambda: rcd.partition_class(S=Sd, cap=cap)),
-              ("recompute", "fl", lambda: rcd.partition_class(X=Xd, cap=cap, sigma2=sigma2)),
+    routes = [("sweeps", "fl", lambda: rcd.partition_class(S=Sd, cap=cap, mode=rcd.MODE_STORED)),
+              ("incremental", "fl", lambda: rcd.partition_class(S=Sd, cap=cap, mode=rcd.MODE_INCREMENTAL)),
+              ("recompute", "fl", lambda: rcd.partition_class(X=Xd, cap=cap, sigma2=sigma2, mode=rcd.MODE_RECOMPUTE)),
               ("graph cut", "gc", lambda: rcd.partition_class_graph_cut(Sd, cap))]
     for name, objective, run in routes:
-        monkeypatch.setenv("RCD_INCREMENTAL", "1" if name == "incremental" else "0")
         a, o, f = run()
         a, o = a.cpu().numpy(), o.cpu().numpy()
         assert np.bincount(a[a >= 0], minlength=K).tolist() == cap.tolist(), name
         assert np.sum(a < 0) == n - cap.sum() and np.all(o[a < 0] == -1), name
-        # The recompute route never holds S: its sweeps rebuild tiles by the matrix cores and its coverage
-        # update rebuilds one column by a dot product, which agree to an ulp.  Once every block holds a copy
-        # of every distinct point, all remaining gains are zero in exact arithmetic and of the size of that
-        # ulp on any fp32 S, so "the same S" decides nothing there: for repeated points that route is
-        # held to the quotas and the objectives only.
-        if not (repeated and name == "recompute"):
-            res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, objective=objective)
-            assert res["rc"] == 0 and res["checked"] == cap.sum(), (name, res)
+        # every route works on one S: the recompute route's tiles and the columns of its coverage update are
+        # the bits of the stored matrix, so groups of repeated points tie exactly there as well
+        res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, objective=objective)
+        assert res["rc"] == 0 and res["checked"] == cap.sum(), (name, res)
         scale = max(1.0, float(S.astype(np.float64).sum()) / K)
         for k in range(K):
             ref = oracle.f_value(S, np.flatnonzero(a == k), objective)

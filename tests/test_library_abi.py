@@ -174,3 +174,48 @@ def test_argument_validation_of_the_later_entry_points(lib):
     for B, rr in ((0, [1, 2]), (8, [1, 0])):
         with pytest.raises(rcd.RcdError):
             rcd.batch_sizes(B, rr)
+
+
+def test_route_argument_and_workspace_query(lib):
+    # rcd_partition_class_mode: the route is an argument; every refusal below happens before any GPU call
+    vp = ctypes.c_void_p
+    cap = np.array([1, 1], dtype=np.int64)
+    obj = np.zeros(2)
+    objp, capp = obj.ctypes.data_as(vp), cap.ctypes.data_as(vp)
+    pcm = lib.rcd_partition_class_mode
+    assert pcm(None, 0, None, 0, 0, 0, 1.0, 10, 2, capp, 9, None, None, objp, None, 0, None) == 4     # unknown mode
+    for mode in (rcd.MODE_STORED, rcd.MODE_INCREMENTAL):
+        assert pcm(None, 0, ctypes.c_void_p(256), 0, 4, 4, 1.0, 10, 2, capp, mode, None, None, objp, None, 0, None) == 1   # no S
+    assert pcm(ctypes.c_void_p(256), 10, None, 0, 0, 0, 1.0, 10, 2, capp, rcd.MODE_RECOMPUTE, None, None, objp,
+               None, 0, None) == 1                                                                        # no X
+    zero = np.array([0, 0], dtype=np.int64)
+    for mode in (rcd.MODE_AUTO, rcd.MODE_STORED, rcd.MODE_RECOMPUTE, rcd.MODE_INCREMENTAL):
+        assert pcm(None, 0, None, 0, 0, 0, 1.0, 0, 2, zero.ctypes.data_as(vp), mode, None, None, objp, None, 0, None) == 0
+
+    # rcd_workspace_bytes: one class, or a data set of unknown class count
+    for n, K, mode in ((1, 1, rcd.MODE_STORED), (5000, 8, rcd.MODE_STORED), (5000, 8, rcd.MODE_RECOMPUTE)):
+        assert rcd.workspace_bytes(n, 0, 512, K, rcd.F32, mode) == rcd.class_workspace_bytes(n, K, mode)
+    w = rcd.workspace_bytes(50000, 5000, 512, 4, rcd.F32, rcd.MODE_STORED)
+    mn, full = rcd.dataset_workspace_bytes(50000, 10, 5000, 4, rcd.MODE_STORED)
+    assert w % 256 == 0 and w >= mn and w >= 5000 * 5000 * 4
+    assert rcd.workspace_bytes(50000, 5000, 512, 4, rcd.BF16, rcd.MODE_STORED) == w          # dtype and d do not enter
+    assert rcd.workspace_bytes(50000, 5000, 64, 4, rcd.F32, rcd.MODE_STORED) == w
+    assert rcd.workspace_bytes(10, 11, 4, 2, 0, 1) == 0 and rcd.workspace_bytes(10, 0, 4, 17, 0, 1) == 0
+    assert rcd.workspace_bytes(0, 0, 4, 2, 0, 1) == 0
+
+    # rcd_release with nothing held is a no-op
+    lib.rcd_release()
+
+
+def test_sweep_chunk_rule_keeps_every_variant_inside_the_workgroups_lds(lib):
+    # the stored-S sweep stages one coverage chunk per slot of the compiled variant that serves nneed blocks;
+    # the chunk rule (in csrc/rcd_state.h) must keep slots x chunk within RCD_SWEEP_LDS_FLOATS for every nneed
+    src = open(os.path.join(ROOT, "paper_2211_00839_amd", "csrc", "rcd_state.h")).read()
+    lds = int(re.search(r"#define RCD_SWEEP_LDS_FLOATS (\d+)", src).group(1))
+    variants = [1, 2, 3, 4, 6, 8, 12, 16]
+    kernels = open(os.path.join(ROOT, "paper_2211_00839_amd", "csrc", "greedy_kernels.hip")).read()
+    assert [int(v) for v in re.findall(r"sweep_rows<(\d+)>\(st, wg\.w", kernels)] == variants
+    for nneed in range(1, 17):
+        slots = min(v for v in variants if v >= nneed)
+        chunk = (lds // slots) // 256 * 256
+        assert slots * chunk <= lds and chunk >= 256
