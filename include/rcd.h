@@ -14,7 +14,8 @@
  *     partition calls), up to four non-blocking streams of its own (the lanes on
  *     which groups of classes advance side by side) and the events of
  *     rcd_profile; per device, a record of one-time set-up (kernel attributes,
- *     the compute-unit count), guarded by a mutex.  Calls from different threads
+ *     the compute-unit count, the address of the static scratch array of
+ *     rcd_similarity_static), guarded by a mutex.  Calls from different threads
  *     are independent as long as their buffers are.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *   - Inputs are never modified.  The return value is an rcd_status; on any
@@ -242,9 +243,9 @@ int rcd_dataset_workspace_bytes(int64_t N, int L, int64_t max_class_n, int K, in
 size_t rcd_workspace_bytes(int64_t N_or_n, int64_t max_class_n, int64_t d, int K, int dt, int mode);
 
 /*
- * One-time set-up for the current device (kernel attributes, compute-unit count).  Optional: every
- * entry point does what it needs on its first call; calling this first keeps that work out of a
- * timed or captured region.
+ * One-time set-up for the current device (kernel attributes, compute-unit count, address of the
+ * static scratch array).  Optional: every entry point does what it needs on its first call; calling
+ * this first keeps that work out of a timed or captured region.
  */
 int rcd_init(void);
 /*
@@ -252,6 +253,20 @@ int rcd_init(void);
  * streams, profiling events).  No call of this thread may be in flight.  Later calls set up again.
  */
 void rcd_release(void);
+
+/*
+ * rcd_similarity for callers that can neither allocate nor pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the
+ * workspace, same kernels, same bits in S; the squared row norms live in a static device array of
+ * the library (RCD_STATIC_MAX_N floats = 256 KB on every device the library runs on, held until
+ * the process ends), so n <= RCD_STATIC_MAX_N, beyond which RCD_ERR_UNSUPPORTED is returned and
+ * nothing is launched.  Calls no allocating routine.  Asynchronous on `stream`.  Every call on a
+ * device uses that device's one array (each call overwrites the entries it needs): two calls whose
+ * kernels may overlap on one device, on different streams or from different threads, race.
+ */
+#define RCD_STATIC_MAX_N 65536
+int rcd_similarity_static(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x,
+                          const int32_t *row_index_dev, float sigma2, float *S_dev, int64_t ld_s, void *stream);
 
 /* Static description of a status code. */
 const char *rcd_strerror(int status);

@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     quota,
     release,
     similarity,
+    similarity_static,
     strerror,
     worker_shards,
     workspace_bytes,
@@ -37,3 +38,4 @@ MODE_STORED = 1
 MODE_RECOMPUTE = 2
 MODE_INCREMENTAL = 3
 MAX_K = 16
+STATIC_MAX_N = 65536

@@ -19,6 +19,7 @@ EXPORTS = [
     "rcd_partition_dataset_graph_cut", "rcd_class_workspace_bytes",
     "rcd_dataset_workspace_bytes", "rcd_strerror", "rcd_last_hip_error", "rcd_last_stats",
     "rcd_profile", "rcd_profile_read", "rcd_partition_class_mode", "rcd_workspace_bytes", "rcd_init", "rcd_release",
+    "rcd_similarity_static",
 ]
 
 
@@ -93,6 +94,8 @@ def load_library():
     lib.rcd_init.argtypes = []
     lib.rcd_release.restype = None
     lib.rcd_release.argtypes = []
+    lib.rcd_similarity_static.restype = i32
+    lib.rcd_similarity_static.argtypes = [vp, i32, i64, i64, i64, vp, f32, vp, i64, vp]
     _lib = lib
     return lib
 
@@ -197,6 +200,19 @@ def init() -> None:
 
 def release() -> None:
     load_library().rcd_release()
+
+
+def similarity_static(X, sigma2: float, out, row_index=None):
+    """rcd_similarity_static: `out` (n, n) float32 is the caller's; nothing is allocated, no workspace."""
+    import torch
+
+    lib = load_library()
+    assert X.dim() == 2 and X.stride(1) == 1
+    n = X.shape[0] if row_index is None else row_index.numel()
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape[0] >= n and out.shape[1] >= n
+    _check(lib.rcd_similarity_static(_dev_ptr(X), _dtype_code(X), n, X.shape[1], X.stride(0), _dev_ptr(row_index),
+                                     float(sigma2), _dev_ptr(out), out.stride(0) if n > 0 else max(n, 1), _stream()))
+    return out
 
 
 def similarity(X, sigma2: float, row_index=None, out=None, workspace=None):

@@ -205,11 +205,13 @@ std::vector<RcdWg> deal_workgroups(const std::vector<RcdClass> &cls, int total)
     return map;
 }
 
-// What is set up once per device (kernel attributes are per device): guarded by one mutex, since partition calls may come from several threads.
+// What is set up once per device (kernel attributes are per device, and so is the address of a
+// __device__ array): guarded by one mutex, since partition calls may come from several threads.
 constexpr int RCD_MAX_DEVICES = 64;
 struct DeviceSetup {
     int cus = 0;               // compute units; 0 = sweep kernel not set up yet
     bool fast_ready = false;   // the matrix-core kernels' LDS limit has been raised
+    float *static_norms = nullptr;   // device address of g_static_norms on this device
 };
 std::mutex g_setup_mutex;
 DeviceSetup g_dev[RCD_MAX_DEVICES];
@@ -249,6 +251,34 @@ int cu_count()
     if (!ds) return 256;
     std::lock_guard<std::mutex> lock(g_setup_mutex);
     return ds->cus > 0 ? ds->cus : 256;
+}
+
+// Scratch of rcd_similarity_static (the squared row norms its kernels pass from one launch to the
+// next): a file-scope device array, so that the entry point needs no workspace and allocates nothing.
+// Every device the library runs on holds its own copy, at its own address, until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress: the kernels are given the address
+// that call returns for the current device, never the name.
+} // namespace
+static __device__ __align__(256) float g_static_norms[RCD_STATIC_MAX_N];
+namespace {
+
+// Device address of g_static_norms on the current device (looked up once per device).
+int static_setup(float **norms)
+{
+    DeviceSetup *ds = device_setup();
+    if (!ds) return RCD_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (!ds->static_norms) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_norms)));
+        if (!ptr) {
+            snprintf(g_hip_err, sizeof g_hip_err, "hipGetSymbolAddress(g_static_norms) returned no address");
+            return RCD_ERR_HIP;
+        }
+        ds->static_norms = static_cast<float *>(ptr);
+    }
+    if (norms) *norms = ds->static_norms;
+    return RCD_OK;
 }
 
 // Fast path of the matrix-core kernels: feature rows that can go straight from global memory
@@ -1144,6 +1174,7 @@ int rcd_init(void)
 {
     RCD_TRY(sweep_setup());
     RCD_TRY(fast_setup());
+    RCD_TRY(static_setup(nullptr));
     return RCD_OK;
 }
 
@@ -1163,6 +1194,21 @@ void rcd_release(void)
         (void)hipHostFree(g_pinned);
         g_pinned = nullptr;
     }
+}
+
+int rcd_similarity_static(const void *X_dev, int dt, int64_t n, int64_t d, int64_t ld_x,
+                          const int32_t *row_index_dev, float sigma2, float *S_dev, int64_t ld_s, void *stream)
+{
+    if (dt != RCD_F32 && dt != RCD_BF16) return RCD_ERR_UNSUPPORTED;
+    if (n < 0 || d < 1 || ld_x < d || ld_s < n || !(sigma2 > 0.f) || !std::isfinite(sigma2)) return RCD_ERR_INVALID_ARG;
+    if (n > RCD_STATIC_MAX_N || d > (int64_t)0x7fffff00) return RCD_ERR_UNSUPPORTED;
+    if (n == 0) return RCD_OK;
+    if (!X_dev || !S_dev) return RCD_ERR_INVALID_ARG;
+    float *norms = nullptr;
+    RCD_TRY(static_setup(&norms));
+    // the same launches as rcd_similarity, the squared row norms in this device's static array
+    return launch_similarity(X_dev, dt, n, d, ld_x, row_index_dev, sigma2, S_dev, ld_s, (int)n, norms,
+                             (hipStream_t)stream);
 }
 
 int rcd_gain_sweep(const float *S_dev, int64_t ld_s, int64_t n, int K, const float *cur_dev,

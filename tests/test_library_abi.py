@@ -176,7 +176,7 @@ def test_argument_validation_of_the_later_entry_points(lib):
             rcd.batch_sizes(B, rr)
 
 
-def test_route_argument_and_workspace_query(lib):
+def test_route_argument_workspace_query_and_static_similarity_refusals(lib):
     # rcd_partition_class_mode: the route is an argument; every refusal below happens before any GPU call
     vp = ctypes.c_void_p
     cap = np.array([1, 1], dtype=np.int64)
@@ -203,6 +203,17 @@ def test_route_argument_and_workspace_query(lib):
     assert rcd.workspace_bytes(10, 11, 4, 2, 0, 1) == 0 and rcd.workspace_bytes(10, 0, 4, 17, 0, 1) == 0
     assert rcd.workspace_bytes(0, 0, 4, 2, 0, 1) == 0
 
+    # rcd_similarity_static: sizes beyond its static scratch and bad arguments are refused before any launch
+    st = lib.rcd_similarity_static
+    assert rcd.STATIC_MAX_N == int(re.search(r"#define RCD_STATIC_MAX_N (\d+)",
+                                             open(os.path.join(ROOT, "include", "rcd.h")).read()).group(1))
+    big = rcd.STATIC_MAX_N + 1
+    assert st(ctypes.c_void_p(256), 0, big, 4, 4, None, 1.0, ctypes.c_void_p(256), big, None) == 4
+    assert st(None, 7, 4, 4, 4, None, 1.0, None, 4, None) == 4
+    assert st(None, 0, 4, 4, 4, None, 0.0, None, 4, None) == 1
+    assert st(None, 0, 4, 4, 2, None, 1.0, None, 4, None) == 1
+    assert st(None, 0, 4, 4, 4, None, 1.0, None, 2, None) == 1
+    assert st(None, 0, 0, 4, 4, None, 1.0, None, 4, None) == 0
     # rcd_release with nothing held is a no-op
     lib.rcd_release()
 
