@@ -63,14 +63,14 @@ def cpu_baseline(ds, budget_steps):
     job_evals = ds.L * n * (n + 1) / 2
     job_time = ds.L * t_sim + job_evals / (evals / t_greedy)
     return {
-        "value": job_evals / job_time,
+        "value": evals / t_greedy,
         "unit": "gain-evals/s",
         "cores": 1,
         "kind": "oracle",
-        "sample": (f"class 0 of the workload (n={n}): its full oracle similarity matrix ({t_sim:.2f} s) and the "
-                   f"first {steps} greedy steps on it ({t_greedy:.2f} s, {evals / t_greedy:.4g} gain-evals/s in "
-                   f"the window); value = whole-job rate extrapolated from both"),
-        "greedy_window_evals_per_s": evals / t_greedy,
+        "sample": (f"class 0 of the workload (n={n}): the first {steps} greedy steps of the oracle on its own "
+                   f"similarity matrix of that class ({evals} gain evaluations in {t_greedy:.2f} s); value = the rate "
+                   f"measured in that window, nothing extrapolated (the matrix itself took {t_sim:.2f} s to build)"),
+        "whole_job_evals_per_s_extrapolated": job_evals / job_time,
         "similarity_s_per_class": t_sim,
         "graph_cut_window_evals_per_s": gc_evals / t_gc if t_gc > 0 else None,
         "graph_cut_window": f"first {gout['steps']} steps of Algorithm 1 with the graph-cut function on the same S ({t_gc:.2f} s)",
@@ -81,92 +81,187 @@ def cpu_baseline(ds, budget_steps):
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def extra_kernels(rcd, si, torch):
-    """The two matrix-core kernels at the shape of one class of the large-class workload
-    (50 000 x 2048 bf16, K = 8): the similarity build, and the first rounds of a greedy run
-    that recomputes S inside every sweep.  Timed with events on the stream they run on."""
+def extra_kernels(rcd, si, torch, only=""):
+    """The matrix-core kernels and the HBM-clean sweep at the shape of one class of the large-class workload
+    (50 000 x 2048 bf16, K = 8): the similarity build (default choice of tiles, and every tile), the bandwidth
+    heuristic, the first rounds of a greedy run that recomputes S inside every sweep, and the same rounds
+    streaming a stored 10 GB S.  Timed with events on the stream they run on.  `only` runs one of them (for a
+    profiler): similarity, similarity_full, bandwidth, recompute, stored_sweep."""
     w = si.WORKLOADS["large"]
     n, d = w.n_c, w.d
     X = si.make_class(seed=w.seed, n=n, d=d, G=w.G, dtype="bf16")
     Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.bfloat16)
     res = {}
-    S = torch.empty((n, n), dtype=torch.float32, device="cuda")
-    ws = torch.empty(n * 4 + 256, dtype=torch.uint8, device="cuda")
-    rcd.similarity(Xd, float(d), out=S, workspace=ws)
     reps = 3
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        rcd.similarity(Xd, float(d), out=S, workspace=ws)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / reps
     tiles = (n + 255) // 256
-    executed = 2.0 * (tiles * (tiles + 1) // 2) * 256 * 256 * d
-    tf = executed / (ms * 1e-3) / 1e12
-    res["similarity_large_class"] = {
-        "kernel": "sim::k_gram_rbf_fast<bf16, mirrored tiles> (+ row norms)", "shape": f"n={n} d={d} bf16 -> fp32 S",
-        "ms": ms,
-        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
-                     "frac": tf / MFMA_PEAK_TFLOPS["bf16"],
-                     "flops": "executed: 2 * 256 * 256 * d per tile, tiles on and above the diagonal only "
-                              "(each also stores its transpose)"},
-        "nominal_2n2d_TFLOPs_per_s": 2.0 * n * n * d / (ms * 1e-3) / 1e12}
-    # the same matrix by the full build (every tile computed, nothing mirrored): the matrix-core pipeline alone
-    os.environ["RCD_SIM_MIRROR"] = "0"
-    try:
-        rcd.similarity(Xd, float(d), out=S, workspace=ws)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
+    want = lambda name: only in ("", name)
+
+    def timed_similarity(mirror_env):
+        S = torch.empty((n, n), dtype=torch.float32, device="cuda")
+        ws = torch.empty(n * 4 + 256, dtype=torch.uint8, device="cuda")
+        if mirror_env is not None:
+            os.environ["RCD_SIM_MIRROR"] = mirror_env
+        try:
             rcd.similarity(Xd, float(d), out=S, workspace=ws)
-        e1.record()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                rcd.similarity(Xd, float(d), out=S, workspace=ws)
+            e1.record()
+            torch.cuda.synchronize()
+        finally:
+            if mirror_env is not None:
+                del os.environ["RCD_SIM_MIRROR"]
+        return e0.elapsed_time(e1) / reps
+
+    if want("similarity"):
+        ms = timed_similarity(None)
+        executed = 2.0 * (tiles * (tiles + 1) // 2) * 256 * 256 * d
+        tf = executed / (ms * 1e-3) / 1e12
+        res["similarity_large_class"] = {
+            "kernel": "sim::k_gram_rbf_fast<bf16, mirrored tiles> (+ row norms)", "shape": f"n={n} d={d} bf16 -> fp32 S",
+            "ms": ms,
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                         "frac": tf / MFMA_PEAK_TFLOPS["bf16"],
+                         "flops": "executed: 2 * 256 * 256 * d per tile, tiles on and above the diagonal only "
+                                  "(each also stores its transpose)"},
+            "nominal_2n2d_TFLOPs_per_s": 2.0 * n * n * d / (ms * 1e-3) / 1e12}
+    if want("similarity_full"):
+        # the same matrix by the full build (every tile computed, nothing mirrored): the matrix-core pipeline alone
+        ms_full = timed_similarity("0")
+        tf_full = 2.0 * tiles * tiles * 256 * 256 * d / (ms_full * 1e-3) / 1e12
+        res.setdefault("similarity_large_class", {})["full_build"] = {
+            "kernel": "sim::k_gram_rbf_fast<bf16, full> (RCD_SIM_MIRROR=0)", "ms": ms_full,
+            "roofline": {"bound": "mfma", "achieved": tf_full, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                         "frac": tf_full / MFMA_PEAK_TFLOPS["bf16"], "flops": "executed: 2 * 256 * 256 * d per tile, every tile"}}
+    if want("bandwidth"):
+        # the paper's bandwidth heuristic on the same class: the same Gram tiles, on and above the diagonal only
+        bws = torch.empty(rcd.load_library().rcd_bandwidth_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        sigma = rcd.bandwidth(Xd, workspace=bws)
         torch.cuda.synchronize()
-    finally:
-        del os.environ["RCD_SIM_MIRROR"]
-    ms_full = e0.elapsed_time(e1) / reps
-    tf_full = 2.0 * tiles * tiles * 256 * 256 * d / (ms_full * 1e-3) / 1e12
-    res["similarity_large_class"]["full_build"] = {
-        "kernel": "sim::k_gram_rbf_fast<bf16, full> (RCD_SIM_MIRROR=0)", "ms": ms_full,
-        "roofline": {"bound": "mfma", "achieved": tf_full, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
-                     "frac": tf_full / MFMA_PEAK_TFLOPS["bf16"], "flops": "executed: 2 * 256 * 256 * d per tile, every tile"}}
-    del S
-    # the paper's bandwidth heuristic on the same class: the same Gram tiles, on and above the diagonal only
-    bws = torch.empty(rcd.load_library().rcd_bandwidth_workspace_bytes(n), dtype=torch.uint8, device="cuda")
-    sigma = rcd.bandwidth(Xd, workspace=bws)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        rcd.bandwidth(Xd, workspace=bws)          # returns a host value: each call ends synchronised
-    ms = 1e3 * (time.perf_counter() - t0) / reps
-    tiles = (n + 255) // 256
-    flops = 2.0 * (tiles * (tiles + 1) // 2) * 256 * 256 * d
-    tf = flops / (ms * 1e-3) / 1e12
-    res["bandwidth_large_class"] = {
-        "kernel": "sim::k_gram_rbf_fast<bf16, distance sum> (+ row norms, sum of tile sums, read-back)",
-        "shape": f"n={n} d={d} bf16 -> sigma = mean pairwise L2 distance", "sigma": sigma, "ms": ms,
-        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
-                     "frac": tf / MFMA_PEAK_TFLOPS["bf16"],
-                     "flops": "2 * 256 * 256 * d per tile, tiles on and above the diagonal"}}
-    del bws
-    # recompute mode: quotas cut to a 48-step window (same ratios), S never stored
-    cap = np.array([2, 2, 4, 4, 6, 6, 8, 16], dtype=np.int64)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            rcd.bandwidth(Xd, workspace=bws)          # returns a host value: each call ends synchronised
+        ms = 1e3 * (time.perf_counter() - t0) / reps
+        flops = 2.0 * (tiles * (tiles + 1) // 2) * 256 * 256 * d
+        tf = flops / (ms * 1e-3) / 1e12
+        res["bandwidth_large_class"] = {
+            "kernel": "sim::k_gram_rbf_fast<bf16, distance sum> (+ row norms, sum of tile sums, read-back)",
+            "shape": f"n={n} d={d} bf16 -> sigma = mean pairwise L2 distance", "sigma": sigma, "ms": ms,
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                         "frac": tf / MFMA_PEAK_TFLOPS["bf16"],
+                         "flops": "2 * 256 * 256 * d per tile, tiles on and above the diagonal"}}
+        del bws
+    if want("recompute"):
+        # recompute mode: quotas cut to a 48-step window (same ratios), S never stored
+        cap = np.array([2, 2, 4, 4, 6, 6, 8, 16], dtype=np.int64)
+        rcd.profile(True)
+        rcd.partition_class(X=Xd, cap=cap, sigma2=float(d))
+        prof = rcd.profile_read()
+        st = rcd.last_stats()
+        rcd.profile(False)
+        flops = 2.0 * st["entries_streamed"] * d
+        tf = flops / (prof["sweep_ms"] * 1e-3) / 1e12 if prof["sweep_ms"] > 0 else 0.0
+        res["recompute_sweep_large_class"] = {
+            "kernel": "rcd_k_round_rc_fast<bf16> (S tiles rebuilt by MFMA inside the gain sweep)",
+            "shape": f"n={n} d={d} bf16, K=8, first {st['steps']} greedy steps, {st['sweeps']} sweeps",
+            "sweep_ms_total": prof["sweep_ms"], "steps_ms_total": prof["steps_ms"], "apply_ms_total": prof["apply_ms"],
+            "useful_evals_per_s": st["useful_evals"] / ((prof["sweep_ms"] + prof["steps_ms"] + prof["apply_ms"]) * 1e-3),
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                         "frac": tf / MFMA_PEAK_TFLOPS["bf16"], "flops": "2 |R| n d per sweep"}}
+    if want("stored_sweep"):
+        res["stored_sweep_large_class"] = stored_sweep_large_class(rcd, torch, Xd, n, d)
+    return res
+
+
+def to_device(torch, ds):
+    if ds.X.dtype == np.uint16:
+        X = torch.from_numpy(ds.X.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        X = torch.from_numpy(ds.X).cuda()
+    return X, torch.from_numpy(ds.labels).cuda()
+
+
+def sweep_roofline(prof, pstats, note=None, n_class=None):
+    """Roofline object of rcd_k_sweep_rows from an instrumented pass (HIP events around every launch)."""
+    sweep_bytes = 4.0 * pstats["entries_streamed"]
+    achieved = sweep_bytes / (prof["sweep_ms"] * 1e-3) / 1e9 if prof["sweep_ms"] > 0 else 0.0
+    r = {"kernel": "rcd_k_sweep_rows (gain sweep of all stale blocks, stored similarity)", "bound": "hbm",
+         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+         "launches": prof["rounds"], "avg_launch_us": 1e3 * prof["sweep_ms"] / max(prof["rounds"], 1),
+         "bytes_per_launch": sweep_bytes / max(prof["rounds"], 1), "sweeps_with_work": pstats["sweeps"]}
+    if n_class:
+        # sum over sweeps of (blocks x candidates) over sum of candidates: blocks evaluated per streamed entry
+        r["avg_blocks_per_sweep"] = pstats["computed_evals"] * n_class / max(pstats["entries_streamed"], 1)
+    if note:
+        r["note"] = note
+    return r
+
+
+def one_config(rcd, si, torch, name, steps, warmup):
+    """Partition wall time of one of the other workloads: by sweeps over a stored S (the route whose kernel the
+    roofline covers) and by RCD_MODE_AUTO (what the library takes when left to choose), same protocol as the
+    headline: inputs in HBM, `warmup` untimed passes, `steps` timed ones between synchronisations."""
+    w = si.WORKLOADS[name]
+    ds = si.make_dataset(w)
+    X, labels = to_device(torch, ds)
+    N, K = ds.X.shape[0], len(ds.r)
+    counts = np.bincount(ds.labels, minlength=ds.L)
+    _, full = rcd.dataset_workspace_bytes(N, ds.L, int(counts.max()), K, rcd.MODE_STORED)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    out = {"workload": describe(w, ds)}
+    for label, mode in (("sweep_route", rcd.MODE_STORED), ("auto_route", rcd.MODE_AUTO)):
+        for _ in range(warmup):
+            rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, mode, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, mode, ws)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / max(steps, 1)
+        st = rcd.last_stats()
+        out[label] = {"route": "RCD_MODE_STORED (one gain sweep per round)" if mode == rcd.MODE_STORED
+                      else "RCD_MODE_AUTO (-> incremental gains: S fits the workspace)",
+                      "partition_wall_time_ms": 1e3 * sec, "useful_evals_per_s": st["useful_evals"] / sec,
+                      "greedy_steps": st["steps"], "sweeps": st["sweeps"], "kernel_launches": st["launches"],
+                      "similarity_entries_read": st["entries_streamed"], "computed_evals": st["computed_evals"]}
+    # instrumented pass of the sweep route: the sweep kernel at this workload's K
     rcd.profile(True)
-    rcd.partition_class(X=Xd, cap=cap, sigma2=float(d))
+    rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, rcd.MODE_STORED, ws)
+    torch.cuda.synchronize()
+    prof = rcd.profile_read()
+    pst = rcd.last_stats()
+    rcd.profile(False)
+    total_S = float(np.sum(counts.astype(np.float64) ** 2) * 4)
+    note = (f"K={K}: {pst['computed_evals'] / max(pst['useful_evals'], 1):.2f} gain evaluations computed per one consumed; "
+            f"all classes' S together {total_S / 1e6:.0f} MB"
+            + (" (fits the 256 MB Infinity Cache: not an HBM-clean figure)" if total_S < 256e6 else ""))
+    out["sweep_kernel"] = sweep_roofline(prof, pst, note, n_class=w.n_c)
+    out["time_split_ms"] = {"similarity": prof["similarity_ms"], "sweep": prof["sweep_ms"], "steps": prof["steps_ms"]}
+    return out
+
+
+def stored_sweep_large_class(rcd, torch, Xd, n, d):
+    """The stored-S sweep kernel where no cache can help: one class of the large workload, S = 10 GB stored, K = 8,
+    the first 48 greedy steps (quotas cut to a window, same ratios): every sweep streams the whole matrix."""
+    cap = np.array([2, 2, 4, 4, 6, 6, 8, 16], dtype=np.int64)
+    S = rcd.similarity(Xd, float(d))
+    ws = torch.empty(rcd.class_workspace_bytes(n, len(cap), rcd.MODE_STORED), dtype=torch.uint8, device="cuda")
+    rcd.partition_class(S=S, cap=cap, workspace=ws)          # warm-up
+    rcd.profile(True)
+    rcd.partition_class(S=S, cap=cap, workspace=ws)
     prof = rcd.profile_read()
     st = rcd.last_stats()
     rcd.profile(False)
-    flops = 2.0 * st["entries_streamed"] * d
-    tf = flops / (prof["sweep_ms"] * 1e-3) / 1e12 if prof["sweep_ms"] > 0 else 0.0
-    res["recompute_sweep_large_class"] = {
-        "kernel": "rcd_k_round_rc_fast<bf16> (S tiles rebuilt by MFMA inside the gain sweep)",
-        "shape": f"n={n} d={d} bf16, K=8, first {st['steps']} greedy steps, {st['sweeps']} sweeps",
-        "sweep_ms_total": prof["sweep_ms"], "steps_ms_total": prof["steps_ms"], "apply_ms_total": prof["apply_ms"],
-        "useful_evals_per_s": st["useful_evals"] / ((prof["sweep_ms"] + prof["steps_ms"] + prof["apply_ms"]) * 1e-3),
-        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
-                     "frac": tf / MFMA_PEAK_TFLOPS["bf16"], "flops": "2 |R| n d per sweep"}}
-    return res
+    r = sweep_roofline(prof, st, "one 10 GB class: 40x the Infinity Cache, every byte from HBM", n_class=n)
+    traffic_file = os.path.join(ROOT, "profiles", "sweep_traffic.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as fh:
+            r["traffic"] = json.load(fh).get("large_class_hbm_bytes_per_launch")
+    return {"shape": f"n={n}, S stored (fp32, {n * n * 4 / 1e9:.0f} GB), K=8, first {st['steps']} greedy steps, "
+                     f"{st['sweeps']} sweeps", "sweep_ms_total": prof["sweep_ms"], "steps_ms_total": prof["steps_ms"],
+            "roofline": r}
 
 
 def large_workload(rcd, si, torch):
@@ -231,6 +326,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the large-class similarity / recompute-sweep lines")
     ap.add_argument("--no-large", action="store_true", help="skip the whole large-class workload (200 GB of workspace)")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the wall times of the other workloads")
+    ap.add_argument("--only", default="", choices=["", "similarity", "similarity_full", "bandwidth", "recompute",
+                                                   "stored_sweep"],
+                    help="run only this kernel of the large-class shape (50 000 x 2048 bf16), for a profiler")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (known traffic) so that rocprofv3 byte counters can be scaled")
     ap.add_argument("--scale", default="", help="L,n_c,d override for quick runs (not a valid bench line)")
@@ -256,6 +355,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "4 device copies of 1 GiB: each reads 2^30 B and writes 2^30 B"}))
+        return
+
+    if args.only:
+        print(json.dumps(extra_kernels(rcd, si, torch, only=args.only)))
         return
 
     w = si.WORKLOADS[args.workload]
@@ -299,21 +402,7 @@ def main():
     prof = rcd.profile_read()
     pstats = rcd.last_stats()
     rcd.profile(False)
-    sweep_bytes = 4.0 * pstats["entries_streamed"]
-    achieved = sweep_bytes / (prof["sweep_ms"] * 1e-3) / 1e9 if prof["sweep_ms"] > 0 else 0.0
-    roofline = {
-        "kernel": "rcd_k_sweep_rows (gain sweep of all stale blocks, stored similarity)",
-        "bound": "hbm",
-        "achieved": achieved,
-        "peak": HBM_PEAK_GBS,
-        "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBS,
-        "traffic": None,
-        "launches": prof["rounds"],
-        "avg_launch_us": 1e3 * prof["sweep_ms"] / max(prof["rounds"], 1),
-        "bytes_per_launch": sweep_bytes / max(prof["rounds"], 1),
-        "sweeps_with_work": pstats["sweeps"],
-    }
+    roofline = sweep_roofline(prof, pstats, n_class=int(counts.max()))
     traffic_file = os.path.join(ROOT, "profiles", "sweep_traffic.json")
     if os.path.exists(traffic_file) and not args.scale and args.workload == "cifar10":
         with open(traffic_file) as fh:
@@ -396,6 +485,10 @@ def main():
         "incremental_route": incremental,
         "graph_cut_route": graph_cut,
     }
+    if not args.scale and not args.no_per_config:
+        # the other workloads of the configuration list (the large one is under `extra`)
+        out["per_config"] = {name: one_config(rcd, si, torch, name, args.steps, args.warmup)
+                             for name in ("tiny", "hetero8", "cifar100") if name != args.workload}
     if not args.scale and not args.no_extra:
         del ws
         out["extra"] = extra_kernels(rcd, si, torch)
