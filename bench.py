@@ -283,10 +283,21 @@ def large_workload(rcd, si, torch):
         torch.cuda.synchronize()
         sec = time.perf_counter() - t0
         st = rcd.last_stats()
-        return {"workload": describe(w, ds), "route": "RCD_MODE_INCREMENTAL, every class's S stored",
-                "partition_wall_time_s": sec, "greedy_steps": st["steps"],
-                "useful_evals_per_s": st["useful_evals"] / sec, "similarity_entries_read": st["entries_streamed"],
-                "workspace_GB": full / 1e9, "runs_timed": 1}
+        out = {"workload": describe(w, ds), "route": "RCD_MODE_INCREMENTAL, every class's S stored",
+               "partition_wall_time_s": sec, "greedy_steps": st["steps"],
+               "useful_evals_per_s": st["useful_evals"] / sec, "similarity_entries_read": st["entries_streamed"],
+               "workspace_GB": full / 1e9, "runs_timed": 1}
+        # the same workload with the graph-cut function (one row of S per step, no update lists)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, workspace=ws, graph_cut=True)
+        torch.cuda.synchronize()
+        gsec = time.perf_counter() - t0
+        gst = rcd.last_stats()
+        out["graph_cut"] = {"route": "rcd_partition_dataset_graph_cut, every class's S stored",
+                            "partition_wall_time_s": gsec, "greedy_steps": gst["steps"],
+                            "useful_evals_per_s": gst["useful_evals"] / gsec, "runs_timed": 1}
+        return out
     except Exception as e:       # e.g. not enough device or host memory on another box
         return {"skipped": repr(e)}
 

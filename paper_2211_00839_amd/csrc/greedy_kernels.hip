@@ -1007,6 +1007,7 @@ extern "C" __global__ void rcd_k_init(const RcdClass *__restrict__ classes)
     for (size_t i = i0; i < ncur; i += stride) st.cur[i] = 0.f;
     for (int i = i0; i < st.ld; i += stride) st.perm[i] = i;
     for (int i = i0; i < st.ld / RCD_TILE_RC; i += stride) st.tilecnt[i] = 0;
+    for (int i = i0; i < RCD_MW_INTS; i += stride) st.mwbuf[i] = 0;
     for (int i = i0; i < st.n && st.assign_out; i += stride) {
         const int oi = st.out_index ? st.out_index[i] : i;
         st.assign_out[oi] = -1;

@@ -82,45 +82,51 @@ rcd_k_inc_update(const RcdClass *__restrict__ classes)
     const int slot = blockIdx.y;
     if (st.done || slot >= st.nneed) return;
     const int k = st.need[slot];
-    const int nd = st.dcount[k];
     const int ld = st.ld;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int v0 = blockIdx.x * 1024 + wave * 256;
-    if (nd <= 0 || v0 >= ld) return;
-    const cci32 dl = (cci32)(inc_dlist(st) + (size_t)k * ld);
-    const ccf32 dold = (ccf32)(inc_dold(st) + (size_t)k * ld);
+    if (st.dcount[k] <= 0 || v0 >= ld) return;
     const ccf32 cur = (ccf32)(st.cur + (size_t)k * ld);
     const gcf32 M = (gcf32)st.M + v0 + lane * 4;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    int e = 0;
-    constexpr int U = 8;      // rows in flight per wave
-    for (; e + U <= nd; e += U) {
-        f32x4 m[U];
-        float cn[U], co[U];
+    // The list is one run of dcount entries, or, when several workgroups share the class's step loop, one
+    // segment per workgroup at the offset of its slice of the samples (ascending j across the segments).
+    const int nseg = st.mw > 1 ? st.mw : 1;
+    for (int sg = 0; sg < nseg; ++sg) {
+        const int nd = st.mw > 1 ? st.mwbuf[MW_PEND + k * RCD_MW_MAX + sg] : st.dcount[k];
+        const size_t off = (size_t)k * ld + (st.mw > 1 ? (size_t)sg * st.mwseg : 0);
+        const cci32 dl = (cci32)(inc_dlist(st) + off);
+        const ccf32 dold = (ccf32)(inc_dold(st) + off);
+        int e = 0;
+        constexpr int U = 8;      // rows in flight per wave
+        for (; e + U <= nd; e += U) {
+            f32x4 m[U];
+            float cn[U], co[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = dl[e + u];
-            cn[u] = cur[j];
-            co[u] = dold[e + u];
-            m[u] = __builtin_nontemporal_load((gcf32x4)(M + (size_t)j * ld));
-        }
+            for (int u = 0; u < U; ++u) {
+                const int j = dl[e + u];
+                cn[u] = cur[j];
+                co[u] = dold[e + u];
+                m[u] = __builtin_nontemporal_load((gcf32x4)(M + (size_t)j * ld));
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            acc[0] += inc_term(m[u].x, cn[u], co[u]);
-            acc[1] += inc_term(m[u].y, cn[u], co[u]);
-            acc[2] += inc_term(m[u].z, cn[u], co[u]);
-            acc[3] += inc_term(m[u].w, cn[u], co[u]);
+            for (int u = 0; u < U; ++u) {
+                acc[0] += inc_term(m[u].x, cn[u], co[u]);
+                acc[1] += inc_term(m[u].y, cn[u], co[u]);
+                acc[2] += inc_term(m[u].z, cn[u], co[u]);
+                acc[3] += inc_term(m[u].w, cn[u], co[u]);
+            }
         }
-    }
-    for (; e < nd; ++e) {
-        const int j = dl[e];
-        const float cn = cur[j], co = dold[e];
-        const f32x4 m = __builtin_nontemporal_load((gcf32x4)(M + (size_t)j * ld));
-        acc[0] += inc_term(m.x, cn, co);
-        acc[1] += inc_term(m.y, cn, co);
-        acc[2] += inc_term(m.z, cn, co);
-        acc[3] += inc_term(m.w, cn, co);
+        for (; e < nd; ++e) {
+            const int j = dl[e];
+            const float cn = cur[j], co = dold[e];
+            const f32x4 m = __builtin_nontemporal_load((gcf32x4)(M + (size_t)j * ld));
+            acc[0] += inc_term(m.x, cn, co);
+            acc[1] += inc_term(m.y, cn, co);
+            acc[2] += inc_term(m.z, cn, co);
+            acc[3] += inc_term(m.w, cn, co);
+        }
     }
     double *g = inc_gains(st) + (size_t)k * ld + v0 + lane * 4;
 #pragma unroll

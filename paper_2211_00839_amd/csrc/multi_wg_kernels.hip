@@ -1,0 +1,473 @@
+// Step loops of large classes run by several workgroups per class (gfx950).
+//
+// The step loops of the incremental-gain route and of the graph-cut function (Algorithm 1's inner
+// while loop: argmin block, argmax sample, coverage / marginal-value update) are latency-bound, and
+// with one workgroup per class a class of 50 000 samples pushes 2.3 MB per step through one compute
+// unit.  Here W workgroups share a class.  Workgroup w owns the w-th slice of the class's samples,
+// both as candidates v (its slice of every block's gains: scanned, updated and struck out by nobody
+// else) and as rows j of the coverage vectors (its slice of cur_k).  What crosses workgroups in a
+// step is small: each workgroup's best candidate (16 bytes), and for the incremental route the
+// entries (j, old, new) of the coverage update, which every workgroup needs for its own candidates.
+// Those go through device-scope stores and loads; the phases of a step are separated by a barrier
+// over the class's W workgroups.
+//
+// The barrier's wait is bounded: a workgroup that has waited longer than `spin_ticks` (100 MHz
+// ticks) raises plans[0].bad = 2 and every workgroup, seeing it, leaves its loop; the kernel always
+// exits and the host reports the failure.  The host sizes the grid to what the device can hold at
+// once (occupancy x compute units) and keeps such launches on one stream, so in normal operation a
+// wait lasts microseconds.
+//
+// Results are those of the one-workgroup loops bit for bit: a gain is a per-candidate sum over the
+// update list in list order (ascending j: the segments of workgroups 0, 1, ... in order), the argmax
+// is the largest value with the lowest index wherever it sits, and f adds the same gains in the
+// same order.  Included by rcd_lib.hip after incremental_kernels.hip.
+#include <hip/hip_runtime.h>
+#include "rcd_state.h"
+
+namespace {
+
+__device__ __forceinline__ float *inc_dnew(const RcdClass &st) { return st.part + 3 * (size_t)st.K * st.ld; }
+
+struct MwBarrier {
+    int32_t *counter;      // this launch's arrival counter
+    int32_t *abort_flag;   // plans[0].bad: 2 = a bounded wait ran out
+    int W, epoch;
+    long long deadline;
+};
+
+// Arrive and wait for the class's W workgroups.  false: the wait ran out here or elsewhere.
+__device__ __forceinline__ bool mw_barrier(MwBarrier &b, int *s_ok)
+{
+    wait_for_my_stores();
+    __syncthreads();
+    b.epoch += 1;
+    if (threadIdx.x == 0) {
+        int ok = 1;
+        if (b.W > 1) {
+            __hip_atomic_fetch_add(b.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int target = b.epoch * b.W;
+            while (__hip_atomic_load(b.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (__hip_atomic_load(b.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 2) { ok = 0; break; }
+                if (wall_clock64() > b.deadline) {
+                    __hip_atomic_store(b.abort_flag, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = 0;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        *s_ok = ok;
+    }
+    __syncthreads();
+    return *s_ok != 0;
+}
+
+struct MwShared {
+    unsigned long long key[RCD_MW_MAX];
+    int v[RCD_MW_MAX];
+    int cnt[RCD_MW_MAX], pre[RCD_MW_MAX + 1];
+    int ok;
+};
+
+// Publish this workgroup's best candidate, meet the others, and leave the class's best in (key, bv):
+// largest key, lowest sample on ties.  slot: this step's 4 x RCD_MW_MAX ints of the exchange area.
+__device__ __forceinline__ bool mw_best_of_class(MwBarrier &bar, MwShared &ms, int32_t *slot, int w, int W,
+                                                 unsigned long long &key, int &bv)
+{
+    const int tid = threadIdx.x;
+    if (W == 1) return true;
+    if (tid == 0) {
+        dev_store((gi32)(slot + 4 * w + 0), (int32_t)(unsigned)(key >> 32));
+        dev_store((gi32)(slot + 4 * w + 1), (int32_t)(unsigned)key);
+        dev_store((gi32)(slot + 4 * w + 2), bv);
+    }
+    if (!mw_barrier(bar, &ms.ok)) return false;
+    if (tid < W) {
+        const unsigned hi = (unsigned)dev_load((gci32)(slot + 4 * tid + 0));
+        const unsigned lo = (unsigned)dev_load((gci32)(slot + 4 * tid + 1));
+        ms.key[tid] = ((unsigned long long)hi << 32) | lo;
+        ms.v[tid] = dev_load((gci32)(slot + 4 * tid + 2));
+    }
+    __syncthreads();
+    key = ms.key[0];
+    bv = ms.v[0];
+    for (int i = 1; i < W; ++i) inc_better(key, bv, ms.key[i], ms.v[i]);
+    return true;
+}
+
+} // namespace
+
+// Greedy steps of the incremental-gain route, W workgroups of 1024 threads per class (wgmap[b] = class,
+// index among the class's workgroups, their count).  Same loop and same limits as rcd_k_inc_steps.
+// parity: 0/1, alternating from launch to launch (which arrival counter this launch uses).
+extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
+rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, const RcdWg *__restrict__ wgmap,
+                   int max_steps, int small_bytes, int parity, long long spin_ticks)
+{
+    constexpr int NT = RCD_STEP_THREADS, NW = NT / 64;
+    __shared__ IncShared sh;
+    __shared__ MwShared ms;
+    const RcdWg wg = wgmap[blockIdx.x];
+    RcdClass &st = classes[wg.cls];
+    const int w = wg.w, W = wg.W;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    {
+        const gci32 g = (gci32)reinterpret_cast<const int32_t *>(&st);
+        int32_t *l = reinterpret_cast<int32_t *>(&sh.d);
+        for (int i = tid; i < (int)(sizeof(RcdClass) / 4); i += NT) l[i] = g[i];
+    }
+    __syncthreads();
+    RcdClass &d = sh.d;
+    if (d.done) {
+        if (w == 0 && tid == 0) st.nneed = 0;
+        return;
+    }
+    const long long tick0 = wall_clock64();
+    MwBarrier bar;
+    bar.counter = d.mwbuf + MW_BAR + (parity & 1);
+    bar.abort_flag = &plans[0].bad;
+    bar.W = W;
+    bar.epoch = 0;
+    bar.deadline = tick0 + spin_ticks;
+    // the counter the next launch will use starts from zero (nobody touches it during this launch)
+    if (w == 0 && tid == 0) dev_store((gi32)(d.mwbuf + MW_BAR + ((parity + 1) & 1)), 0);
+    // everyone holds its copy of the descriptor before anyone may write it back
+    if (!mw_barrier(bar, &ms.ok)) return;
+
+    const int K = d.K, n = d.n, ld = d.ld, total = d.total;
+    if (tid < d.nneed) d.valid[d.need[tid]] = 1;      // the update launch brought these blocks' gains up to date
+    __syncthreads();
+    double *G = inc_gains(d);
+    int32_t *dlist = inc_dlist(d);
+    float *dold = inc_dold(d), *dnew = inc_dnew(d);
+    const gcf32 M = (gcf32)d.M;
+    // my slice of the samples: candidates v and coverage rows j alike
+    const int mwseg = d.mwseg;
+    const int v0 = min(w * mwseg, ld), v1 = min(v0 + mwseg, ld), nv = max(min(v1, n) - v0, 0);
+    const int seg = ((v1 - v0 + NW - 1) / NW + 255) / 256 * 256;      // j range of a wave inside the slice
+    // lists up to this many rows are applied right here, every workgroup on its own candidates
+    const long long row_bytes = (long long)ld * 4;
+    const int small = (int)max(4LL, min((long long)INC_SMALL, (long long)small_bytes * W / row_bytes));
+    int32_t *slot = d.mwbuf + MW_SLOT;
+    int32_t *segcnt = d.mwbuf + MW_SEGCNT;
+
+    int nR = d.nR, t = d.t, done = 0;
+    const int t0 = t;
+    bool alive = true;
+    long long useful = 0, entries = 0, computed = 0, sweeps = 0;
+    for (;;) {
+        if (t >= total) { done = 1; break; }
+        if (t - t0 >= max_steps) break;
+        int js = -1;
+        double fbest = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (d.cnt[k] >= d.cap[k]) continue;
+            const double fk = d.f[k];
+            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
+        }
+        if (js < 0) { done = 1; break; }
+        if (!d.valid[js]) break;
+
+        // ---- argmax over my slice of the block's gains, then over the class
+        double best = INC_LIVE_ABOVE;
+        int bv = 0x7fffffff;
+        inc_scan<NT>(G + (size_t)js * ld + v0, nv, tid, best, bv);
+        if (bv != 0x7fffffff) bv += v0;
+        unsigned long long key = inc_key(best);
+        inc_wave_best(key, bv);
+        if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
+        __syncthreads();
+        key = sh.wkey[0];
+        bv = sh.wv[0];
+#pragma unroll
+        for (int i = 1; i < NW; ++i) inc_better(key, bv, sh.wkey[i], sh.wv[i]);
+        if (!mw_best_of_class(bar, ms, slot, w, W, key, bv)) { alive = false; break; }
+        best = inc_value(key);
+        const int vstar = bv;
+        if (vstar >= n) { done = 1; break; }          // no candidate left (cannot happen while t < total <= n)
+
+        // ---- bookkeeping (every workgroup keeps the same copy of the state) and outputs (workgroup 0)
+        __syncthreads();                              // everyone has read the block state this step was decided on
+        if (tid == 0) {
+            d.cnt[js] += 1;
+            d.f[js] += best;
+            if (w == 0) {
+                const int oi = d.out_index ? d.out_index[vstar] : vstar;
+                d.assign_out[oi] = js;
+                if (d.order_out) d.order_out[oi] = t;
+            }
+        }
+        if (tid < K && vstar >= v0 && vstar < v1) G[(size_t)tid * ld + vstar] = INC_TAKEN;
+
+        // ---- coverage update on my rows j: cur_js(j) = max(cur_js(j), S(j, v*)); the changed j, ascending,
+        //      with their old and new values, go to my segment of the block's list (at my slice's offset)
+        const gcf32 row = M + (size_t)vstar * ld;
+        float *cur = d.cur + (size_t)js * ld;
+        const int j_begin = min(v0 + wave * seg, v1), j_end = min(j_begin + seg, v1);
+        int cnt = 0;
+        for (int s = j_begin + lane * 4; s < j_end; s += 256) {
+            const f32x4 m = *(gcf32x4)(row + s);
+            const f32x4 c = *(const f32x4 *)(cur + s);
+            cnt += (m.x > c.x) + (m.y > c.y) + (m.z > c.z) + (m.w > c.w);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
+        if (lane == 0) sh.wcount[wave] = cnt;
+        __syncthreads();
+        int base = 0, mine = 0;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int c = sh.wcount[i];
+            if (i < wave) base += c;
+            mine += c;
+        }
+        if (cnt > 0) {
+            gi32 dl = (gi32)(dlist + (size_t)js * ld + v0);
+            gf32 dol = (gf32)(dold + (size_t)js * ld + v0), dnw = (gf32)(dnew + (size_t)js * ld + v0);
+            for (int s = j_begin + lane * 4; s < j_end; s += 256) {
+                const f32x4 m = *(gcf32x4)(row + s);
+                const f32x4 c = *(const f32x4 *)(cur + s);
+                const bool ch[4] = {m.x > c.x, m.y > c.y, m.z > c.z, m.w > c.w};
+                const int here = ch[0] + ch[1] + ch[2] + ch[3];
+                int incl = here;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int up = __shfl_up(incl, off);
+                    if (lane >= off) incl += up;
+                }
+                int pos = base + incl - here;
+                const float mv[4] = {m.x, m.y, m.z, m.w}, cv[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (ch[q]) {
+                        dev_store(dl + pos, s + q);
+                        dev_store(dol + pos, cv[q]);
+                        dev_store(dnw + pos, mv[q]);
+                        ++pos;
+                    }
+                if (here) {
+                    f32x4 r;
+                    r.x = fmaxf(c.x, m.x); r.y = fmaxf(c.y, m.y); r.z = fmaxf(c.z, m.z); r.w = fmaxf(c.w, m.w);
+                    *(f32x4 *)(cur + s) = r;
+                }
+                base += __shfl(incl, 63);
+            }
+        }
+        if (tid == 0) dev_store((gi32)(segcnt + w), mine);
+        if (!mw_barrier(bar, &ms.ok)) { alive = false; break; }
+
+        // ---- the whole list: every workgroup's segment, in order
+        if (tid < W) ms.cnt[tid] = W > 1 ? dev_load((gci32)(segcnt + tid)) : mine;
+        __syncthreads();
+        int nd = 0;
+        for (int i = 0; i < W; ++i) nd += ms.cnt[i];
+        entries += (long long)nd * n;
+        computed += nR - 1;
+        if (nd > small) {
+            // long list: left to the update launch (which walks the segments), the block sits out until then
+            if (tid == 0) {
+                d.valid[js] = 0;
+                d.dcount[js] = nd;
+                d.mwbuf[MW_PEND + js * RCD_MW_MAX + w] = mine;
+            }
+            sweeps += 1;
+        } else if (nd > 0) {
+            if (tid == 0) {
+                int run = 0;
+                for (int i = 0; i < W; ++i) { ms.pre[i] = run; run += ms.cnt[i]; }
+                ms.pre[W] = run;
+            }
+            __syncthreads();
+            for (int e = tid; e < nd; e += NT) {
+                int i = 0;
+                while (e >= ms.pre[i + 1]) ++i;
+                const size_t at = (size_t)js * ld + (size_t)i * mwseg + (e - ms.pre[i]);
+                sh.sj[e] = dev_load((gci32)(dlist + at));
+                sh.sold[e] = dev_load((gcf32)(dold + at));
+                sh.snew[e] = dev_load((gcf32)(dnew + at));
+            }
+            __syncthreads();
+            double *gj = G + (size_t)js * ld;
+            for (int vv = v0 + tid * 4; vv < v1; vv += NT * 4) {
+                double acc[4] = {0.0, 0.0, 0.0, 0.0};
+                for (int e0 = 0; e0 < nd; e0 += 8) {
+                    f32x4 m[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (e0 + u < nd) m[u] = *(gcf32x4)(M + (size_t)sh.sj[e0 + u] * ld + vv);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (e0 + u < nd) {
+                            const float cn = sh.snew[e0 + u], co = sh.sold[e0 + u];
+                            acc[0] += inc_term(m[u].x, cn, co);
+                            acc[1] += inc_term(m[u].y, cn, co);
+                            acc[2] += inc_term(m[u].z, cn, co);
+                            acc[3] += inc_term(m[u].w, cn, co);
+                        }
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) gj[vv + c] += acc[c];
+            }
+        }
+        useful += nR;
+        nR -= 1;
+        ++t;
+        __syncthreads();           // the step's writes (gains, LDS state) are in place
+    }
+    if (!alive) return;            // a bounded wait ran out: plans[0].bad says so, nothing is written back
+
+    // ---- the descriptor, by workgroup 0 (every workgroup holds the same copy)
+    __syncthreads();
+    if (w != 0) return;
+    if (tid == 0) {
+        int nneed = 0;
+        if (!done)
+            for (int k = 0; k < K; ++k)
+                if (d.cnt[k] < d.cap[k] && !d.valid[k]) d.need[nneed++] = k;
+        d.nneed = nneed;
+        d.stat_sweeps += sweeps;
+        d.stat_entries += entries;
+        d.stat_computed += computed;
+        d.stat_steps += t - t0;
+        d.stat_useful += useful;
+        d.nR = nR;
+        d.t = t;
+        d.done = done;
+        d.stat_ticks += wall_clock64() - tick0;
+        if (done) __hip_atomic_fetch_add(&plans[0].ndone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    {
+        constexpr int first = (int)(offsetof(RcdClass, nR) / 4);
+        gi32 g = (gi32)reinterpret_cast<int32_t *>(&st);
+        const int32_t *l = reinterpret_cast<const int32_t *>(&sh.d);
+        for (int i = first + tid; i < (int)(sizeof(RcdClass) / 4); i += NT) g[i] = l[i];
+    }
+}
+
+// Greedy steps with the graph-cut function, W workgroups per class: a step is a scan of my slice of
+// the block's marginal values, one exchange of the workgroups' best candidates, and row v* of S taken
+// off my slice.  One barrier per step; the exchange slots alternate with the step's parity.
+extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
+rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, const RcdWg *__restrict__ wgmap,
+                  int max_steps, int parity, long long spin_ticks)
+{
+    constexpr int NT = RCD_STEP_THREADS, NW = NT / 64;
+    __shared__ IncShared sh;
+    __shared__ MwShared ms;
+    const RcdWg wg = wgmap[blockIdx.x];
+    RcdClass &st = classes[wg.cls];
+    const int w = wg.w, W = wg.W;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    {
+        const gci32 g = (gci32)reinterpret_cast<const int32_t *>(&st);
+        int32_t *l = reinterpret_cast<int32_t *>(&sh.d);
+        for (int i = tid; i < (int)(sizeof(RcdClass) / 4); i += NT) l[i] = g[i];
+    }
+    __syncthreads();
+    RcdClass &d = sh.d;
+    if (d.done) return;
+    const long long tick0 = wall_clock64();
+    MwBarrier bar;
+    bar.counter = d.mwbuf + MW_BAR + (parity & 1);
+    bar.abort_flag = &plans[0].bad;
+    bar.W = W;
+    bar.epoch = 0;
+    bar.deadline = tick0 + spin_ticks;
+    if (w == 0 && tid == 0) dev_store((gi32)(d.mwbuf + MW_BAR + ((parity + 1) & 1)), 0);
+    if (!mw_barrier(bar, &ms.ok)) return;
+
+    const int K = d.K, n = d.n, ld = d.ld, total = d.total;
+    double *G = inc_gains(d);
+    const gcf32 M = (gcf32)d.M;
+    const int mwseg = d.mwseg;
+    const int v0 = min(w * mwseg, ld), v1 = min(v0 + mwseg, ld), nv = max(min(v1, n) - v0, 0);
+    int nR = d.nR, t = d.t, done = 0;
+    const int t0 = t;
+    bool alive = true;
+    long long useful = 0;
+    for (;;) {
+        if (t >= total) { done = 1; break; }
+        if (t - t0 >= max_steps) break;
+        int js = -1;
+        double fbest = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (d.cnt[k] >= d.cap[k]) continue;
+            const double fk = d.f[k];
+            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
+        }
+        if (js < 0) { done = 1; break; }
+        double *g = G + (size_t)js * ld;
+        double best = INC_LIVE_ABOVE;
+        int bv = 0x7fffffff;
+        inc_scan<NT>(g + v0, nv, tid, best, bv);
+        if (bv != 0x7fffffff) bv += v0;
+        unsigned long long key = inc_key(best);
+        inc_wave_best(key, bv);
+        if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
+        __syncthreads();
+        key = sh.wkey[0];
+        bv = sh.wv[0];
+#pragma unroll
+        for (int i = 1; i < NW; ++i) inc_better(key, bv, sh.wkey[i], sh.wv[i]);
+        if (!mw_best_of_class(bar, ms, d.mwbuf + MW_SLOT + (t & 1) * 4 * RCD_MW_MAX, w, W, key, bv)) { alive = false; break; }
+        best = inc_value(key);
+        const int vstar = bv;
+        if (vstar >= n) { done = 1; break; }
+        __syncthreads();                              // everyone has read the block state this step was decided on
+        if (tid == 0) {
+            d.cnt[js] += 1;
+            d.f[js] += best;
+            if (w == 0) {
+                const int oi = d.out_index ? d.out_index[vstar] : vstar;
+                d.assign_out[oi] = js;
+                if (d.order_out) d.order_out[oi] = t;
+            }
+        }
+        // ---- every marginal value of the block drops by 2 S(v, v*), on my slice
+        const gcf32 row = M + (size_t)vstar * ld;
+        for (int vv = v0 + tid * 4; vv < v1; vv += NT * 4) {
+            const f32x4 m = *(gcf32x4)(row + vv);
+            double o[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = g[vv + c];
+            g[vv] = o[0] - 2.0 * (double)m.x;
+            g[vv + 1] = o[1] - 2.0 * (double)m.y;
+            g[vv + 2] = o[2] - 2.0 * (double)m.z;
+            g[vv + 3] = o[3] - 2.0 * (double)m.w;
+        }
+        // v* leaves every block's candidates: its owner strikes it out (in the served block, the thread that has
+        // just updated that entry: its own earlier store to the same address)
+        if (vstar >= v0 && vstar < v1) {
+            if (((vstar - v0) >> 2) % NT == tid) g[vstar] = INC_TAKEN;
+            if (tid < K && tid != js) G[(size_t)tid * ld + vstar] = INC_TAKEN;
+        }
+        useful += nR;
+        nR -= 1;
+        ++t;
+        __syncthreads();
+    }
+    if (!alive) return;
+    __syncthreads();
+    if (w != 0) return;
+    if (tid == 0) {
+        d.nneed = 0;
+        d.stat_steps += t - t0;
+        d.stat_useful += useful;
+        d.stat_entries += (long long)(t - t0) * n;
+        d.nR = nR;
+        d.t = t;
+        d.done = done;
+        d.stat_ticks += wall_clock64() - tick0;
+        if (done) __hip_atomic_fetch_add(&plans[0].ndone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    {
+        constexpr int first = (int)(offsetof(RcdClass, nR) / 4);
+        gi32 gd = (gi32)reinterpret_cast<int32_t *>(&st);
+        const int32_t *l = reinterpret_cast<const int32_t *>(&sh.d);
+        for (int i = first + tid; i < (int)(sizeof(RcdClass) / 4); i += NT) gd[i] = l[i];
+    }
+}

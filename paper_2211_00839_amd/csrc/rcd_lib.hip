@@ -18,6 +18,7 @@
 #include "split_kernels.hip"
 #include "recompute_kernels.hip"
 #include "incremental_kernels.hip"
+#include "multi_wg_kernels.hip"
 
 static_assert(RCD_KMAX == RCD_MAX_K, "public and internal block limits differ");
 
@@ -97,6 +98,7 @@ size_t class_state_bytes(int64_t n, int K, bool stored)
     b += up256((size_t)K * ld * 4);              // gain
     b += up256(ld / RCD_TILE_RC * 4);            // tilecnt
     b += up256(ld * 4);                          // perm
+    b += up256(RCD_MW_INTS * 4);                 // exchange area of the multi-workgroup step loops
     return b;
 }
 
@@ -148,6 +150,7 @@ bool carve_class(Carver &cv, RcdClass &c, int64_t n, int K, const int64_t *cap, 
     c.gain = cv.take<float>((size_t)K * ld);
     c.tilecnt = cv.take<int32_t>(ld / RCD_TILE_RC);
     c.perm = cv.take<int32_t>(ld);
+    c.mwbuf = cv.take<int32_t>(RCD_MW_INTS);
     int64_t total = 0;
     for (int k = 0; k < K; ++k) {
         c.cap[k] = (int)cap[k];
@@ -341,6 +344,15 @@ int ensure_side_streams(int count)
     return RCD_OK;
 }
 
+// Do the step loops of the incremental and graph-cut routes share a class among several workgroups?  From
+// RCD_MW_MIN_N samples in the largest class on (0 switches it off): below that one workgroup's step is short
+// enough that the barriers between the phases would cost more than they save.
+bool multi_wg_wanted(int64_t max_n)
+{
+    const int min_n = env_int("RCD_MW_MIN_N", 16384, 0, 0x7fffffff);
+    return min_n > 0 && max_n >= min_n;
+}
+
 // One group of classes on one stream.  The host keeps a few batches of rounds
 // queued ahead of the device: start(), then enqueue_batch() while fewer than
 // `depth` batches are unread and poll() to read the oldest one's progress record,
@@ -355,6 +367,10 @@ struct Lane {
     bool incremental = false;   // stored S with incrementally maintained gains
     bool graph_cut = false;     // graph-cut function: stored S, the step loop keeps its own gains current
     int gc_max_steps = 4096;    // steps per class and launch (bounds a launch's duration)
+    // several workgroups per class for the step loops of large classes (incremental gains, graph cut)
+    bool mw = false;
+    int mw_wgs = 0, mw_launch = 0;
+    long long mw_spin_ticks = 200000000;   // bound of a grid-barrier wait, 100 MHz ticks (2 s)
     dim3 update_grid;
     int inc_small_bytes = 512 << 10;   // update lists up to this many bytes of rows are applied by the step loop itself
     int inc_max_steps = 64;     // steps per class and launch: a class that waits for the update launch waits for the whole lane
@@ -370,6 +386,28 @@ struct Lane {
     int64_t prof_done = 0;   // batches whose timing events have been read
 
     RcdPlan *pinned(int64_t b) const { return g_pinned + 2 * (RCD_SLOTS * slot + (int)(b % RCD_SLOTS)); }
+
+    // The step loops of the incremental and graph-cut routes: one workgroup per class, or, for large classes,
+    // several (the launches of a lane alternate between the two arrival counters of the grid barrier).
+    void launch_inc_steps()
+    {
+        if (mw)
+            hipLaunchKernelGGL(rcd_k_inc_steps_mw, dim3(mw_wgs), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                               g->plan_dev, (const RcdWg *)g->wgmap_dev, inc_max_steps, inc_small_bytes, mw_launch++ & 1,
+                               mw_spin_ticks);
+        else
+            hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                               g->plan_dev, inc_max_steps, inc_small_bytes);
+    }
+    void launch_gc_steps()
+    {
+        if (mw)
+            hipLaunchKernelGGL(rcd_k_gc_steps_mw, dim3(mw_wgs), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                               g->plan_dev, (const RcdWg *)g->wgmap_dev, gc_max_steps, mw_launch++ & 1, mw_spin_ticks);
+        else
+            hipLaunchKernelGGL(rcd_k_gc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
+                               g->plan_dev, gc_max_steps);
+    }
 
     void launch_apply(int rn)
     {
@@ -433,6 +471,45 @@ struct Lane {
         const int shared_steps = std::min(32, std::max(4, 400000 / std::max(max_n, 1)));
         inc_max_steps = env_int("RCD_INC_STEPS", ncls > 1 ? shared_steps : 4096, 1, 1 << 20);
         inc_small_bytes = env_int("RCD_INC_SMALL_KB", 512, 1, 1 << 20) * 1024;
+        mw = false;
+        if ((graph_cut || incremental) && multi_wg_wanted(max_n)) {
+            // Workgroups per class: what the device can hold at once, shared evenly, at most RCD_MW_MAX and no
+            // more than one per RCD_MW_SLICE (2048) samples; classes too small to share keep one workgroup in the same launch.
+            int per_cu = 0;
+            const void *kfn = graph_cut ? reinterpret_cast<const void *>(rcd_k_gc_steps_mw)
+                                        : reinterpret_cast<const void *>(rcd_k_inc_steps_mw);
+            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kfn, RCD_STEP_THREADS, 0));
+            const int capacity = std::max(per_cu, 0) * cu_count();
+            // (measured on one 50 000-sample class: graph cut 1418 ms with one workgroup, 537 / 408 / 374 / 411 ms with
+            // 4 / 8 / 16 / 32: past 16 the barrier's arrivals cost more than the shorter slices save)
+            const int w_max = std::min(env_int("RCD_MW_MAX_WGS", 16, 1, RCD_MW_MAX), capacity / std::max(ncls, 1));
+            const int mw_slice = env_int("RCD_MW_SLICE", 2048, 256, 1 << 20) / 256 * 256;    // samples a workgroup owns, at least
+            if (w_max >= 2) {
+                std::vector<RcdWg> map;
+                for (int i = 0; i < ncls; ++i) {
+                    RcdClass &c = g->host[i];
+                    int W = std::min(w_max, std::max(1, c.ld / mw_slice));
+                    int seg = ((c.ld + W - 1) / W + 255) / 256 * 256;
+                    W = (c.ld + seg - 1) / seg;               // no empty slice
+                    c.mw = W;
+                    c.mwseg = seg;
+                    for (int w = 0; w < W; ++w) map.push_back(RcdWg{i, w, W, 0});
+                }
+                if ((int)map.size() <= capacity && (int)map.size() <= RCD_MAX_SWEEP_WGS) {
+                    mw = true;
+                    mw_wgs = (int)map.size();
+                    mw_launch = 0;
+                    mw_spin_ticks = (long long)env_int("RCD_MW_SPIN_MS", 2000, 0, 60000) * 100000LL;
+                    // a shared class steps about four times faster: four times the steps per call for the same wait
+                    if (ncls > 1)
+                        inc_max_steps = env_int("RCD_INC_STEPS", std::min(64, std::max(8, 1600000 / std::max(max_n, 1))), 1, 1 << 20);
+                    HIP_TRY(hipMemcpyAsync(g->wgmap_dev, map.data(), sizeof(RcdWg) * map.size(), hipMemcpyHostToDevice, stream));
+                    HIP_TRY(hipMemcpyAsync(g->classes_dev, g->host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
+                } else {
+                    for (RcdClass &c : g->host) { c.mw = 0; c.mwseg = 0; }
+                }
+            }
+        }
         if (graph_cut) {
             // initial marginal values = column sums of S without the diagonal
             hipLaunchKernelGGL(rcd_k_gc_init, dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls), dim3(256), 0, stream,
@@ -453,13 +530,11 @@ struct Lane {
         }
         // step loop number 1 (the bootstrap) and its apply; step loop r+2 follows round r's sweep
         if (graph_cut)
-            hipLaunchKernelGGL(rcd_k_gc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev,
-                               gc_max_steps);
+            launch_gc_steps();
         else if (recompute)
             hipLaunchKernelGGL(rcd_k_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev, g->plan_dev);
         else if (incremental)
-            hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
-                               g->plan_dev, inc_max_steps, inc_small_bytes);
+            launch_inc_steps();
         else
             hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                g->plan_dev);
@@ -527,11 +602,9 @@ struct Lane {
             ++round_no;
             if (pe) (void)hipEventRecord((*pe)[3 * r + 1], stream);
             if (graph_cut)
-                hipLaunchKernelGGL(rcd_k_gc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
-                                   g->plan_dev, gc_max_steps);
+                launch_gc_steps();
             else if (incremental)
-                hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
-                                   g->plan_dev, inc_max_steps, inc_small_bytes);
+                launch_inc_steps();
             else if (!recompute)
                 hipLaunchKernelGGL(rcd_k_steps_rows, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                    g->plan_dev);
@@ -576,6 +649,12 @@ struct Lane {
         if (prof) { read_events(polled); prof_done = polled + 1; }
         const RcdPlan *seen = pinned(polled);
         ++polled;
+        if (seen[0].bad == 2) {
+            finished = true;
+            snprintf(g_hip_err, sizeof g_hip_err,
+                     "a workgroup's bounded wait at a grid barrier of the multi-workgroup step loop ran out");
+            return RCD_ERR_HIP;
+        }
         if (seen[0].bad) { finished = true; return RCD_ERR_BAD_SIMILARITY; }
         if (std::max(seen[0].ndone, seen[1].ndone) >= ncls) finished = true;
         return RCD_OK;
@@ -1493,6 +1572,9 @@ static int partition_dataset_impl(int objective, const void *X_dev, int dt, int6
             // busy for milliseconds per round, so there is nothing for a second lane to hide.
             int nl = 1;
             if (stored && !g_profile_on) nl = std::min(live, env_int("RCD_LANES", 2, 1, RCD_MAX_LANES));
+            // step loops that share classes among workgroups wait for one another inside the kernel: such
+            // launches stay on one stream, so that two of them never compete for the compute units
+            if (stored && (objective == 1 || incremental || auto_incremental) && multi_wg_wanted(max_count)) nl = 1;
             std::vector<Group> lanes(nl);
             {
                 std::vector<double> cum(live + 1, 0.0);

@@ -18,6 +18,8 @@
 #define RCD_SWEEP_THREADS (64 * RCD_SWEEP_WAVES)
 #define RCD_SWEEP_LDS_FLOATS 32768   // LDS of a stored-S sweep workgroup: coverage of the evaluated blocks, one chunk of j
 #define RCD_STEP_THREADS 1024
+#define RCD_MW_MAX 32        // most workgroups that share one class in the multi-workgroup step loops
+#define RCD_MW_INTS 1024     // ints of a class's exchange area for those loops (layout: MW_* below)
 
 // The stored-S sweep kernel exists for these numbers of evaluated blocks; a sweep of nneed blocks runs
 // the smallest variant that holds them and stages that many coverage vectors (the spare slots repeat the
@@ -44,6 +46,7 @@ struct RcdClass {
     int32_t *assign_out; // caller's arrays (global indexing through out_index)
     int32_t *order_out;  // nullable
     const int32_t *out_index; // nullable: position of local sample v in the caller's arrays
+    int32_t *mwbuf;      // RCD_MW_INTS ints: what the workgroups of a multi-workgroup step loop exchange
     const void *X;       // recompute mode: features (rows picked through x_index)
     const int32_t *x_index; // nullable
     int64_t ldx64;
@@ -55,6 +58,7 @@ struct RcdClass {
     int32_t target_items;       // sweep workgroups this class should be split into
     int32_t incremental;        // stored S: gains are kept current by update lists instead of sweeps
     int32_t objective;          // 0 = facility location, 1 = graph cut (stored S, its own step loop)
+    int32_t mw, mwseg;          // workgroups that share this class's step loop (0 or 1: one) and the samples each owns
     // ---- evolving
     int32_t nR;          // unassigned samples = live columns
     int32_t t;           // steps taken
@@ -78,6 +82,16 @@ struct RcdClass {
     int64_t stat_steps, stat_sweeps, stat_entries, stat_useful, stat_computed;
     int64_t stat_ticks;  // 100 MHz ticks spent inside the step loops
 };
+
+// Exchange area of the multi-workgroup step loops, in ints from RcdClass::mwbuf.
+enum {
+    MW_BAR = 0,                                  // two arrival counters, used by alternate launches
+    MW_SLOT = 16,                                // 2 x RCD_MW_MAX x 4: a workgroup's best key (hi, lo), sample, unused
+    MW_SEGCNT = MW_SLOT + 2 * 4 * RCD_MW_MAX,    // RCD_MW_MAX: update-list entries each workgroup found this step
+    MW_PEND = MW_SEGCNT + RCD_MW_MAX,            // RCD_KMAX x RCD_MW_MAX: segment lengths of block k's pending list
+    MW_END = MW_PEND + RCD_KMAX * RCD_MW_MAX
+};
+static_assert(MW_END <= RCD_MW_INTS, "exchange area too small");
 
 // Work layout of one round.  Two of these are kept (launch r reads buffer r&1
 // and writes the other), followed in memory by two int32 prefix[ncls+1] arrays:

@@ -237,7 +237,7 @@ def test_full_size_cifar100_incremental_every_step(rcd):
             assert res["checked"] == 500
 
 
-def test_large_class_one_full_class_incremental(rcd):
+def test_large_class_one_full_class_incremental(rcd, monkeypatch):
     # one whole class of the large workload (50 000 x 2048 bf16, K = 8, its real quotas): similarity
     # stored (10 GB), all 50 000 steps by the incremental route; the oracle referees sampled steps
     # on the same S and the objectives come from the definition
@@ -255,6 +255,12 @@ def test_large_class_one_full_class_incremental(rcd):
     assert stats["steps"] == w.n_c
     assert np.bincount(a, minlength=8).tolist() == cap.tolist()
     assert np.array_equal(np.sort(o), np.arange(w.n_c))
+    # a class this size is shared among several workgroups: the one-workgroup loop must give the same bits
+    monkeypatch.setenv("RCD_MW_MIN_N", "0")
+    a1, o1, f1 = rcd.partition_class(S=S, cap=cap, mode=rcd.MODE_INCREMENTAL)
+    monkeypatch.delenv("RCD_MW_MIN_N")
+    print(f"  one workgroup: stats {rcd.last_stats()}", flush=True)
+    assert np.array_equal(a1.cpu().numpy(), a) and np.array_equal(o1.cpu().numpy(), o) and np.array_equal(f1, f)
     # objectives from the definition, on the device (max over the block's columns, summed in double)
     for k in (0, 7):
         members = torch.from_numpy(np.flatnonzero(a == k)).cuda()
@@ -351,7 +357,7 @@ def test_full_size_graph_cut_workloads(rcd, name):
         assert np.bincount(assign[idx], minlength=len(ds.r)).tolist() == oracle.quota(len(idx), ds.r).tolist()
 
 
-def test_large_class_one_full_class_graph_cut(rcd):
+def test_large_class_one_full_class_graph_cut(rcd, monkeypatch):
     # one whole class of the large workload (50 000 x 2048 bf16, K = 8, its real quotas), S stored, all
     # 50 000 steps with the graph-cut function; invariants, objectives from the definition (on the device,
     # in double), the first pick from its closed form, the oracle's referee on sampled steps
@@ -367,6 +373,12 @@ def test_large_class_one_full_class_graph_cut(rcd):
     assert stats["steps"] == w.n_c
     assert np.bincount(a, minlength=8).tolist() == cap.tolist()
     assert np.array_equal(np.sort(o), np.arange(w.n_c))
+    # a class this size is shared among several workgroups: the one-workgroup loop must give the same bits
+    monkeypatch.setenv("RCD_MW_MIN_N", "0")
+    a1, o1, f1 = rcd.partition_class_graph_cut(S, cap)
+    monkeypatch.delenv("RCD_MW_MIN_N")
+    print(f"  one workgroup: stats {rcd.last_stats()}", flush=True)
+    assert np.array_equal(a1.cpu().numpy(), a) and np.array_equal(o1.cpu().numpy(), o) and np.array_equal(f1, f)
     # empty blocks: the marginal value of v is its column sum without the diagonal, so the first pick is its argmax
     colsum = S.double().sum(dim=0) - S.diagonal().double()
     first = int(np.flatnonzero(o == 0)[0])
