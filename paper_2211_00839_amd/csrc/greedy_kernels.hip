@@ -170,9 +170,12 @@ __device__ __forceinline__ void sweep_rows(const RcdClass &st, int w, int W, flo
         const int j0 = c * JC;
         const int len = min(JC, ld - j0);   // a multiple of 256
         if (c > 0) __syncthreads();
-#pragma unroll
+        // (a plain loop over the slots: unrolled, the KS source pointers were kept in registers all at once
+        // and the sixteen-slot variant spilled)
+#pragma unroll 1
         for (int i = 0; i < KS; ++i) {
-            const gcf32 src = cur + (size_t)kb[i] * ld + j0;
+            const int k = __builtin_amdgcn_readfirstlane(st.need[i < nneed ? i : nneed - 1]);
+            const gcf32 src = cur + (size_t)k * ld + j0;
             for (int e = tid * 4; e < len; e += RCD_SWEEP_THREADS * 4)
                 *(f32x4 __attribute__((address_space(3))) *)(lcur + i * JC + e) = *(gcf32x4)(src + e);
         }

@@ -28,6 +28,16 @@ namespace {
 
 __device__ __forceinline__ float *inc_dnew(const RcdClass &st) { return st.part + 3 * (size_t)st.K * st.ld; }
 
+// A pointer that is the same in every lane, moved into scalar registers (it then costs no vector register
+// and addresses become "scalar base + lane offset").
+template <typename P> __device__ __forceinline__ P *mw_uniform(P *q)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(q);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));
+    return reinterpret_cast<P *>(((unsigned long long)hi << 32) | lo);
+}
+
 struct MwBarrier {
     int32_t *counter;      // this launch's arrival counter
     int32_t *abort_flag;   // plans[0].bad: 2 = a bounded wait ran out
@@ -138,19 +148,21 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
     const int K = d.K, n = d.n, ld = d.ld, total = d.total;
     if (tid < d.nneed) d.valid[d.need[tid]] = 1;      // the update launch brought these blocks' gains up to date
     __syncthreads();
-    double *G = inc_gains(d);
-    int32_t *dlist = inc_dlist(d);
-    float *dold = inc_dold(d), *dnew = inc_dnew(d);
-    const gcf32 M = (gcf32)d.M;
+    double *G = mw_uniform(inc_gains(d));
+    int32_t *dlist = mw_uniform(inc_dlist(d));
+    float *dold = mw_uniform(inc_dold(d)), *dnew = mw_uniform(inc_dnew(d));
+    const gcf32 M = (gcf32)mw_uniform(d.M);
+    float *cur_all = mw_uniform(d.cur);
     // my slice of the samples: candidates v and coverage rows j alike
-    const int mwseg = d.mwseg;
+    const int mwseg = __builtin_amdgcn_readfirstlane(d.mwseg);
     const int v0 = min(w * mwseg, ld), v1 = min(v0 + mwseg, ld), nv = max(min(v1, n) - v0, 0);
     const int seg = ((v1 - v0 + NW - 1) / NW + 255) / 256 * 256;      // j range of a wave inside the slice
     // lists up to this many rows are applied right here, every workgroup on its own candidates
     const long long row_bytes = (long long)ld * 4;
     const int small = (int)max(4LL, min((long long)INC_SMALL, (long long)small_bytes * W / row_bytes));
-    int32_t *slot = d.mwbuf + MW_SLOT;
-    int32_t *segcnt = d.mwbuf + MW_SEGCNT;
+    int32_t *mwbuf = mw_uniform(d.mwbuf);
+    int32_t *slot = mwbuf + MW_SLOT;
+    int32_t *segcnt = mwbuf + MW_SEGCNT;
 
     int nR = d.nR, t = d.t, done = 0;
     const int t0 = t;
@@ -203,13 +215,34 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
         // ---- coverage update on my rows j: cur_js(j) = max(cur_js(j), S(j, v*)); the changed j, ascending,
         //      with their old and new values, go to my segment of the block's list (at my slice's offset)
         const gcf32 row = M + (size_t)vstar * ld;
-        float *cur = d.cur + (size_t)js * ld;
+        float *cur = cur_all + (size_t)js * ld;
         const int j_begin = min(v0 + wave * seg, v1), j_end = min(j_begin + seg, v1);
+        // A wave's range is at most two pieces of 256 when the slice is at most 8192 samples (the usual case):
+        // both pieces of the row and of the coverage vector are fetched in one trip and kept for the write-out.
+        const bool two = seg <= 512;
+        f32x4 pm[2], pc[2];
         int cnt = 0;
-        for (int s = j_begin + lane * 4; s < j_end; s += 256) {
-            const f32x4 m = *(gcf32x4)(row + s);
-            const f32x4 c = *(const f32x4 *)(cur + s);
-            cnt += (m.x > c.x) + (m.y > c.y) + (m.z > c.z) + (m.w > c.w);
+        if (two) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int s = j_begin + lane * 4 + p * 256;
+                if (s < j_end) {
+                    pm[p] = *(gcf32x4)(row + s);
+                    pc[p] = *(const f32x4 *)(cur + s);
+                } else {
+                    pm[p] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    pc[p] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+                cnt += (pm[p].x > pc[p].x) + (pm[p].y > pc[p].y) + (pm[p].z > pc[p].z) + (pm[p].w > pc[p].w);
+        } else {
+            for (int s = j_begin + lane * 4; s < j_end; s += 256) {
+                const f32x4 m = *(gcf32x4)(row + s);
+                const f32x4 c = *(const f32x4 *)(cur + s);
+                cnt += (m.x > c.x) + (m.y > c.y) + (m.z > c.z) + (m.w > c.w);
+            }
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
@@ -225,9 +258,8 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
         if (cnt > 0) {
             gi32 dl = (gi32)(dlist + (size_t)js * ld + v0);
             gf32 dol = (gf32)(dold + (size_t)js * ld + v0), dnw = (gf32)(dnew + (size_t)js * ld + v0);
-            for (int s = j_begin + lane * 4; s < j_end; s += 256) {
-                const f32x4 m = *(gcf32x4)(row + s);
-                const f32x4 c = *(const f32x4 *)(cur + s);
+            // one piece: its changed entries, in ascending j, appended at `base`; the piece's coverage raised
+            auto write_piece = [&](int s, const f32x4 &m, const f32x4 &c) {
                 const bool ch[4] = {m.x > c.x, m.y > c.y, m.z > c.z, m.w > c.w};
                 const int here = ch[0] + ch[1] + ch[2] + ch[3];
                 int incl = here;
@@ -252,6 +284,16 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
                     *(f32x4 *)(cur + s) = r;
                 }
                 base += __shfl(incl, 63);
+            };
+            if (two) {
+#pragma unroll
+                for (int p = 0; p < 2; ++p) write_piece(j_begin + lane * 4 + p * 256, pm[p], pc[p]);
+            } else {
+                for (int s = j_begin + lane * 4; s < j_end; s += 256) {
+                    const f32x4 m = *(gcf32x4)(row + s);
+                    const f32x4 c = *(const f32x4 *)(cur + s);
+                    write_piece(s, m, c);
+                }
             }
         }
         if (tid == 0) dev_store((gi32)(segcnt + w), mine);
@@ -269,7 +311,7 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
             if (tid == 0) {
                 d.valid[js] = 0;
                 d.dcount[js] = nd;
-                d.mwbuf[MW_PEND + js * RCD_MW_MAX + w] = mine;
+                mwbuf[MW_PEND + js * RCD_MW_MAX + w] = mine;
             }
             sweeps += 1;
         } else if (nd > 0) {
@@ -289,25 +331,45 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
             }
             __syncthreads();
             double *gj = G + (size_t)js * ld;
-            for (int vv = v0 + tid * 4; vv < v1; vv += NT * 4) {
-                double acc[4] = {0.0, 0.0, 0.0, 0.0};
-                for (int e0 = 0; e0 < nd; e0 += 8) {
-                    f32x4 m[8];
+            // a thread's candidates: pieces of four, NT * 4 apart; two pieces are served by the same trips (a slice
+            // a little over NT * 4 samples, the usual case, is then one round instead of two)
+            for (int vv = v0 + tid * 4; vv < v1; vv += NT * 8) {
+                const int vw = vv + NT * 4;
+                const bool second = vw < v1;
+                double acc[2][4] = {{0.0, 0.0, 0.0, 0.0}, {0.0, 0.0, 0.0, 0.0}};
+                for (int e0 = 0; e0 < nd; e0 += 4) {
+                    // (every element is loaded, past the list's end from its last row and without a second piece
+                    // from the first again: a register left undefined on some path would be kept alive around the
+                    // whole step loop)
+                    f32x4 m[2][4];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (e0 + u < nd) m[u] = *(gcf32x4)(M + (size_t)sh.sj[e0 + u] * ld + vv);
+                    for (int u = 0; u < 4; ++u) {
+                        const gcf32 r = M + (size_t)sh.sj[min(e0 + u, nd - 1)] * ld;
+                        m[0][u] = *(gcf32x4)(r + vv);
+                        m[1][u] = *(gcf32x4)(r + (second ? vw : vv));
+                    }
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
+                    for (int u = 0; u < 4; ++u)
                         if (e0 + u < nd) {
                             const float cn = sh.snew[e0 + u], co = sh.sold[e0 + u];
-                            acc[0] += inc_term(m[u].x, cn, co);
-                            acc[1] += inc_term(m[u].y, cn, co);
-                            acc[2] += inc_term(m[u].z, cn, co);
-                            acc[3] += inc_term(m[u].w, cn, co);
+                            acc[0][0] += inc_term(m[0][u].x, cn, co);
+                            acc[0][1] += inc_term(m[0][u].y, cn, co);
+                            acc[0][2] += inc_term(m[0][u].z, cn, co);
+                            acc[0][3] += inc_term(m[0][u].w, cn, co);
+                            if (second) {
+                                acc[1][0] += inc_term(m[1][u].x, cn, co);
+                                acc[1][1] += inc_term(m[1][u].y, cn, co);
+                                acc[1][2] += inc_term(m[1][u].z, cn, co);
+                                acc[1][3] += inc_term(m[1][u].w, cn, co);
+                            }
                         }
                 }
 #pragma unroll
-                for (int c = 0; c < 4; ++c) gj[vv + c] += acc[c];
+                for (int c = 0; c < 4; ++c) gj[vv + c] += acc[0][c];
+                if (second) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) gj[vw + c] += acc[1][c];
+                }
             }
         }
         useful += nR;
@@ -428,15 +490,30 @@ rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, c
         }
         // ---- every marginal value of the block drops by 2 S(v, v*), on my slice
         const gcf32 row = M + (size_t)vstar * ld;
-        for (int vv = v0 + tid * 4; vv < v1; vv += NT * 4) {
-            const f32x4 m = *(gcf32x4)(row + vv);
-            double o[4];
+        for (int vv = v0 + tid * 4; vv < v1; vv += NT * 8) {
+            // two pieces of four per thread and trip (a slice a little over NT * 4 samples is one round)
+            const int vw = vv + NT * 4;
+            const bool second = vw < v1;
+            const f32x4 m0 = *(gcf32x4)(row + vv);
+            f32x4 m1 = m0;
+            double o0[4], o1[4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) o[c] = g[vv + c];
-            g[vv] = o[0] - 2.0 * (double)m.x;
-            g[vv + 1] = o[1] - 2.0 * (double)m.y;
-            g[vv + 2] = o[2] - 2.0 * (double)m.z;
-            g[vv + 3] = o[3] - 2.0 * (double)m.w;
+            for (int c = 0; c < 4; ++c) o0[c] = g[vv + c];
+            if (second) {
+                m1 = *(gcf32x4)(row + vw);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o1[c] = g[vw + c];
+            }
+            g[vv] = o0[0] - 2.0 * (double)m0.x;
+            g[vv + 1] = o0[1] - 2.0 * (double)m0.y;
+            g[vv + 2] = o0[2] - 2.0 * (double)m0.z;
+            g[vv + 3] = o0[3] - 2.0 * (double)m0.w;
+            if (second) {
+                g[vw] = o1[0] - 2.0 * (double)m1.x;
+                g[vw + 1] = o1[1] - 2.0 * (double)m1.y;
+                g[vw + 2] = o1[2] - 2.0 * (double)m1.z;
+                g[vw + 3] = o1[3] - 2.0 * (double)m1.w;
+            }
         }
         // v* leaves every block's candidates: its owner strikes it out (in the served block, the thread that has
         // just updated that entry: its own earlier store to the same address)
