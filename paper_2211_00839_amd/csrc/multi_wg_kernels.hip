@@ -8,14 +8,14 @@
 // else) and as rows j of the coverage vectors (its slice of cur_k).  What crosses workgroups in a
 // step is small: each workgroup's best candidate (16 bytes), and for the incremental route the
 // entries (j, old, new) of the coverage update, which every workgroup needs for its own candidates.
-// Those go through device-scope stores and loads; the phases of a step are separated by a barrier
-// over the class's W workgroups.
+// Those go through device-scope stores and loads; the phases of a step are separated by an exchange
+// among the class's W workgroups (every workgroup posts 16 bytes and polls until it has read everybody's
+// post for that exchange: see MwExchange), which is the step's barrier and carries its payload at once.
 //
-// The barrier's wait is bounded: a workgroup that has waited longer than `spin_ticks` (100 MHz
-// ticks) raises plans[0].bad = 2 and every workgroup, seeing it, leaves its loop; the kernel always
-// exits and the host reports the failure.  The host sizes the grid to what the device can hold at
-// once (occupancy x compute units) and keeps such launches on one stream, so in normal operation a
-// wait lasts microseconds.
+// Every wait is bounded: a workgroup that has waited longer than `spin_ticks` (100 MHz ticks) raises
+// plans[0].bad = 2 and every workgroup, seeing it, leaves its loop; the kernel always exits and the
+// host reports the failure.  The host sizes the grid to what the device can hold at once (occupancy x
+// compute units) and keeps such launches on one stream, so in normal operation a wait lasts microseconds.
 //
 // Results are those of the one-workgroup loops bit for bit: a gain is a per-candidate sum over the
 // update list in list order (ascending j: the segments of workgroups 0, 1, ... in order), the argmax
@@ -38,70 +38,98 @@ template <typename P> __device__ __forceinline__ P *mw_uniform(P *q)
     return reinterpret_cast<P *>(((unsigned long long)hi << 32) | lo);
 }
 
-struct MwBarrier {
-    int32_t *counter;      // this launch's arrival counter
-    int32_t *abort_flag;   // plans[0].bad: 2 = a bounded wait ran out
-    int W, epoch;
+// An exchange among the W workgroups of a class: every workgroup posts three ints, then every workgroup
+// has everybody's.  Also the barrier between the phases of a step (what a workgroup wrote with
+// device-scope stores before posting is visible to whoever has read its post).
+//
+// A post is one 16-byte device-scope store {a, b, c, tag} into the workgroup's slot of the bank the
+// exchange's number selects (two banks, used alternately: nobody can be two exchanges ahead of anybody,
+// because completing one needs everybody's post for it).  tag = a hash of the exchange's number and of
+// the three ints, never zero: a reader takes a slot only when its tag fits its contents and the current
+// exchange, so a slot still holding an older post, a freshly zeroed one, or a (never observed) torn
+// 16-byte read is simply read again.  No counter, no atomic: a store, then polls.
+// The exchange numbers of one partition call rise from launch to launch (epoch0 from the host).
+// Every wait is bounded by `deadline`; when it runs out the flag *abort_flag is set to 2 and every
+// workgroup that sees it gives up.
+struct MwExchange {
+    int32_t *banks;        // 2 x RCD_MW_MAX x 4 ints
+    int32_t *abort_flag;   // plans[0].bad
+    int W, w;
+    unsigned epoch;
     long long deadline;
 };
 
-// Arrive and wait for the class's W workgroups.  false: the wait ran out here or elsewhere.
-__device__ __forceinline__ bool mw_barrier(MwBarrier &b, int *s_ok)
-{
-    wait_for_my_stores();
-    __syncthreads();
-    b.epoch += 1;
-    if (threadIdx.x == 0) {
-        int ok = 1;
-        if (b.W > 1) {
-            __hip_atomic_fetch_add(b.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int target = b.epoch * b.W;
-            while (__hip_atomic_load(b.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-                if (__hip_atomic_load(b.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 2) { ok = 0; break; }
-                if (wall_clock64() > b.deadline) {
-                    __hip_atomic_store(b.abort_flag, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    ok = 0;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-            }
-        }
-        *s_ok = ok;
-    }
-    __syncthreads();
-    return *s_ok != 0;
-}
-
 struct MwShared {
-    unsigned long long key[RCD_MW_MAX];
-    int v[RCD_MW_MAX];
-    int cnt[RCD_MW_MAX], pre[RCD_MW_MAX + 1];
+    int a[RCD_MW_MAX], b[RCD_MW_MAX], c[RCD_MW_MAX];
+    int pre[RCD_MW_MAX + 1];
     int ok;
 };
 
-// Publish this workgroup's best candidate, meet the others, and leave the class's best in (key, bv):
-// largest key, lowest sample on ties.  slot: this step's 4 x RCD_MW_MAX ints of the exchange area.
-__device__ __forceinline__ bool mw_best_of_class(MwBarrier &bar, MwShared &ms, int32_t *slot, int w, int W,
-                                                 unsigned long long &key, int &bv)
+__device__ __forceinline__ unsigned mw_tag(unsigned epoch, unsigned a, unsigned b, unsigned c)
+{
+    return ((epoch * 0x9E3779B1u) ^ a ^ ((b << 11) | (b >> 21)) ^ ((c << 22) | (c >> 10)) ^ 0xA5A5A5A5u) | 1u;
+}
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4 dev_load4(const int32_t *p)
+{
+    i32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ void dev_store4i(int32_t *p, int a, int b, int c, int d)
+{
+    const i32x4 v = {a, b, c, d};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
+// Every thread of the workgroup calls this with the same (a, b, c).  On return ms.a/b/c[0..W) hold the posts.
+__device__ __forceinline__ bool mw_exchange(MwExchange &x, MwShared &ms, int a, int b, int c)
 {
     const int tid = threadIdx.x;
-    if (W == 1) return true;
-    if (tid == 0) {
-        dev_store((gi32)(slot + 4 * w + 0), (int32_t)(unsigned)(key >> 32));
-        dev_store((gi32)(slot + 4 * w + 1), (int32_t)(unsigned)key);
-        dev_store((gi32)(slot + 4 * w + 2), bv);
+    wait_for_my_stores();      // what I wrote for the others has left this compute unit ...
+    __syncthreads();           // ... and so has what the rest of my workgroup wrote
+    x.epoch += 1;
+    if (x.W == 1) {
+        if (tid == 0) { ms.a[0] = a; ms.b[0] = b; ms.c[0] = c; ms.ok = 1; }
+        __syncthreads();
+        return true;
     }
-    if (!mw_barrier(bar, &ms.ok)) return false;
-    if (tid < W) {
-        const unsigned hi = (unsigned)dev_load((gci32)(slot + 4 * tid + 0));
-        const unsigned lo = (unsigned)dev_load((gci32)(slot + 4 * tid + 1));
-        ms.key[tid] = ((unsigned long long)hi << 32) | lo;
-        ms.v[tid] = dev_load((gci32)(slot + 4 * tid + 2));
+    int32_t *bank = x.banks + (x.epoch & 1u) * (4 * RCD_MW_MAX);
+    if (tid == 0) dev_store4i(bank + 4 * x.w, a, b, c, (int)mw_tag(x.epoch, (unsigned)a, (unsigned)b, (unsigned)c));
+    if (tid < 64) {
+        int ok = 0;
+        for (;;) {
+            i32x4 s = {0, 0, 0, 0};
+            if (tid < x.W) s = dev_load4(bank + 4 * tid);
+            const bool good = tid >= x.W || (unsigned)s.w == mw_tag(x.epoch, (unsigned)s.x, (unsigned)s.y, (unsigned)s.z);
+            if (__all(good)) {
+                if (tid < x.W) { ms.a[tid] = s.x; ms.b[tid] = s.y; ms.c[tid] = s.z; }
+                ok = 1;
+                break;
+            }
+            if (__hip_atomic_load(x.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 2) break;
+            if (wall_clock64() > x.deadline) {
+                __hip_atomic_store(x.abort_flag, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (tid == 0) ms.ok = ok;
     }
     __syncthreads();
-    key = ms.key[0];
-    bv = ms.v[0];
-    for (int i = 1; i < W; ++i) inc_better(key, bv, ms.key[i], ms.v[i]);
+    return ms.ok != 0;
+}
+
+// The class's best candidate from the workgroups' best: largest key, lowest sample on ties.
+__device__ __forceinline__ bool mw_best_of_class(MwExchange &x, MwShared &ms, unsigned long long &key, int &bv)
+{
+    if (x.W == 1) return true;
+    if (!mw_exchange(x, ms, (int)(unsigned)(key >> 32), (int)(unsigned)key, bv)) return false;
+    key = ((unsigned long long)(unsigned)ms.a[0] << 32) | (unsigned)ms.b[0];
+    bv = ms.c[0];
+    for (int i = 1; i < x.W; ++i)
+        inc_better(key, bv, ((unsigned long long)(unsigned)ms.a[i] << 32) | (unsigned)ms.b[i], ms.c[i]);
     return true;
 }
 
@@ -109,10 +137,10 @@ __device__ __forceinline__ bool mw_best_of_class(MwBarrier &bar, MwShared &ms, i
 
 // Greedy steps of the incremental-gain route, W workgroups of 1024 threads per class (wgmap[b] = class,
 // index among the class's workgroups, their count).  Same loop and same limits as rcd_k_inc_steps.
-// parity: 0/1, alternating from launch to launch (which arrival counter this launch uses).
+// epoch0: exchanges done by this call's earlier launches (an upper bound; the numbers only have to rise).
 extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
 rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, const RcdWg *__restrict__ wgmap,
-                   int max_steps, int small_bytes, int parity, long long spin_ticks)
+                   int max_steps, int small_bytes, unsigned epoch0, long long spin_ticks)
 {
     constexpr int NT = RCD_STEP_THREADS, NW = NT / 64;
     __shared__ IncShared sh;
@@ -134,16 +162,15 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
         return;
     }
     const long long tick0 = wall_clock64();
-    MwBarrier bar;
-    bar.counter = d.mwbuf + MW_BAR + (parity & 1);
+    MwExchange bar;
+    bar.banks = mw_uniform(d.mwbuf) + MW_SLOT;
     bar.abort_flag = &plans[0].bad;
     bar.W = W;
-    bar.epoch = 0;
+    bar.w = w;
+    bar.epoch = epoch0;
     bar.deadline = tick0 + spin_ticks;
-    // the counter the next launch will use starts from zero (nobody touches it during this launch)
-    if (w == 0 && tid == 0) dev_store((gi32)(d.mwbuf + MW_BAR + ((parity + 1) & 1)), 0);
     // everyone holds its copy of the descriptor before anyone may write it back
-    if (!mw_barrier(bar, &ms.ok)) return;
+    if (!mw_exchange(bar, ms, 0, 0, 0)) return;
 
     const int K = d.K, n = d.n, ld = d.ld, total = d.total;
     if (tid < d.nneed) d.valid[d.need[tid]] = 1;      // the update launch brought these blocks' gains up to date
@@ -161,8 +188,6 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
     const long long row_bytes = (long long)ld * 4;
     const int small = (int)max(4LL, min((long long)INC_SMALL, (long long)small_bytes * W / row_bytes));
     int32_t *mwbuf = mw_uniform(d.mwbuf);
-    int32_t *slot = mwbuf + MW_SLOT;
-    int32_t *segcnt = mwbuf + MW_SEGCNT;
 
     int nR = d.nR, t = d.t, done = 0;
     const int t0 = t;
@@ -194,7 +219,7 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
         bv = sh.wv[0];
 #pragma unroll
         for (int i = 1; i < NW; ++i) inc_better(key, bv, sh.wkey[i], sh.wv[i]);
-        if (!mw_best_of_class(bar, ms, slot, w, W, key, bv)) { alive = false; break; }
+        if (!mw_best_of_class(bar, ms, key, bv)) { alive = false; break; }
         best = inc_value(key);
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }          // no candidate left (cannot happen while t < total <= n)
@@ -296,14 +321,10 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
                 }
             }
         }
-        if (tid == 0) dev_store((gi32)(segcnt + w), mine);
-        if (!mw_barrier(bar, &ms.ok)) { alive = false; break; }
-
-        // ---- the whole list: every workgroup's segment, in order
-        if (tid < W) ms.cnt[tid] = W > 1 ? dev_load((gci32)(segcnt + tid)) : mine;
-        __syncthreads();
+        // ---- the whole list: every workgroup's segment, in order (the exchange carries the segment lengths)
+        if (!mw_exchange(bar, ms, mine, 0, 0)) { alive = false; break; }
         int nd = 0;
-        for (int i = 0; i < W; ++i) nd += ms.cnt[i];
+        for (int i = 0; i < W; ++i) nd += ms.a[i];
         entries += (long long)nd * n;
         computed += nR - 1;
         if (nd > small) {
@@ -317,7 +338,7 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
         } else if (nd > 0) {
             if (tid == 0) {
                 int run = 0;
-                for (int i = 0; i < W; ++i) { ms.pre[i] = run; run += ms.cnt[i]; }
+                for (int i = 0; i < W; ++i) { ms.pre[i] = run; run += ms.a[i]; }
                 ms.pre[W] = run;
             }
             __syncthreads();
@@ -410,10 +431,10 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
 
 // Greedy steps with the graph-cut function, W workgroups per class: a step is a scan of my slice of
 // the block's marginal values, one exchange of the workgroups' best candidates, and row v* of S taken
-// off my slice.  One barrier per step; the exchange slots alternate with the step's parity.
+// off my slice.  One exchange per step.
 extern "C" __global__ void __launch_bounds__(RCD_STEP_THREADS)
 rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, const RcdWg *__restrict__ wgmap,
-                  int max_steps, int parity, long long spin_ticks)
+                  int max_steps, unsigned epoch0, long long spin_ticks)
 {
     constexpr int NT = RCD_STEP_THREADS, NW = NT / 64;
     __shared__ IncShared sh;
@@ -432,14 +453,14 @@ rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, c
     RcdClass &d = sh.d;
     if (d.done) return;
     const long long tick0 = wall_clock64();
-    MwBarrier bar;
-    bar.counter = d.mwbuf + MW_BAR + (parity & 1);
+    MwExchange bar;
+    bar.banks = mw_uniform(d.mwbuf) + MW_SLOT;
     bar.abort_flag = &plans[0].bad;
     bar.W = W;
-    bar.epoch = 0;
+    bar.w = w;
+    bar.epoch = epoch0;
     bar.deadline = tick0 + spin_ticks;
-    if (w == 0 && tid == 0) dev_store((gi32)(d.mwbuf + MW_BAR + ((parity + 1) & 1)), 0);
-    if (!mw_barrier(bar, &ms.ok)) return;
+    if (!mw_exchange(bar, ms, 0, 0, 0)) return;
 
     const int K = d.K, n = d.n, ld = d.ld, total = d.total;
     double *G = inc_gains(d);
@@ -474,7 +495,7 @@ rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, c
         bv = sh.wv[0];
 #pragma unroll
         for (int i = 1; i < NW; ++i) inc_better(key, bv, sh.wkey[i], sh.wv[i]);
-        if (!mw_best_of_class(bar, ms, d.mwbuf + MW_SLOT + (t & 1) * 4 * RCD_MW_MAX, w, W, key, bv)) { alive = false; break; }
+        if (!mw_best_of_class(bar, ms, key, bv)) { alive = false; break; }
         best = inc_value(key);
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }

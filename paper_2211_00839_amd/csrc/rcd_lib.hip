@@ -369,7 +369,8 @@ struct Lane {
     int gc_max_steps = 4096;    // steps per class and launch (bounds a launch's duration)
     // several workgroups per class for the step loops of large classes (incremental gains, graph cut)
     bool mw = false;
-    int mw_wgs = 0, mw_launch = 0;
+    int mw_wgs = 0;
+    unsigned mw_epoch = 0;      // exchanges the earlier launches of this call may have used
     long long mw_spin_ticks = 200000000;   // bound of a grid-barrier wait, 100 MHz ticks (2 s)
     dim3 update_grid;
     int inc_small_bytes = 512 << 10;   // update lists up to this many bytes of rows are applied by the step loop itself
@@ -388,12 +389,16 @@ struct Lane {
     RcdPlan *pinned(int64_t b) const { return g_pinned + 2 * (RCD_SLOTS * slot + (int)(b % RCD_SLOTS)); }
 
     // The step loops of the incremental and graph-cut routes: one workgroup per class, or, for large classes,
-    // several (the launches of a lane alternate between the two arrival counters of the grid barrier).
+    // several (a launch numbers its exchanges from where the launch before it may have stopped: one exchange at
+    // the start, then two per step on the incremental route, one with the graph-cut function).
     void launch_inc_steps()
     {
+        const unsigned epoch0 = mw_epoch;
+        mw_epoch += 2u * (unsigned)inc_max_steps + 8u;
+        (void)epoch0;
         if (mw)
             hipLaunchKernelGGL(rcd_k_inc_steps_mw, dim3(mw_wgs), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
-                               g->plan_dev, (const RcdWg *)g->wgmap_dev, inc_max_steps, inc_small_bytes, mw_launch++ & 1,
+                               g->plan_dev, (const RcdWg *)g->wgmap_dev, inc_max_steps, inc_small_bytes, epoch0,
                                mw_spin_ticks);
         else
             hipLaunchKernelGGL(rcd_k_inc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
@@ -401,9 +406,12 @@ struct Lane {
     }
     void launch_gc_steps()
     {
+        const unsigned epoch0 = mw_epoch;
+        mw_epoch += (unsigned)gc_max_steps + 8u;
+        (void)epoch0;
         if (mw)
             hipLaunchKernelGGL(rcd_k_gc_steps_mw, dim3(mw_wgs), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
-                               g->plan_dev, (const RcdWg *)g->wgmap_dev, gc_max_steps, mw_launch++ & 1, mw_spin_ticks);
+                               g->plan_dev, (const RcdWg *)g->wgmap_dev, gc_max_steps, epoch0, mw_spin_ticks);
         else
             hipLaunchKernelGGL(rcd_k_gc_steps, dim3(ncls), dim3(RCD_STEP_THREADS), 0, stream, g->classes_dev,
                                g->plan_dev, gc_max_steps);
@@ -498,7 +506,7 @@ struct Lane {
                 if ((int)map.size() <= capacity && (int)map.size() <= RCD_MAX_SWEEP_WGS) {
                     mw = true;
                     mw_wgs = (int)map.size();
-                    mw_launch = 0;
+                    mw_epoch = 0;
                     mw_spin_ticks = (long long)env_int("RCD_MW_SPIN_MS", 2000, 0, 60000) * 100000LL;
                     // a shared class steps about four times faster: four times the steps per call for the same wait
                     if (ncls > 1)

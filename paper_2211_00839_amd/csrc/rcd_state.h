@@ -83,12 +83,10 @@ struct RcdClass {
     int64_t stat_ticks;  // 100 MHz ticks spent inside the step loops
 };
 
-// Exchange area of the multi-workgroup step loops, in ints from RcdClass::mwbuf.
+// Exchange area of the multi-workgroup step loops, in ints from RcdClass::mwbuf (zeroed when a call starts).
 enum {
-    MW_BAR = 0,                                  // two arrival counters, used by alternate launches
-    MW_SLOT = 16,                                // 2 x RCD_MW_MAX x 4: a workgroup's best key (hi, lo), sample, unused
-    MW_SEGCNT = MW_SLOT + 2 * 4 * RCD_MW_MAX,    // RCD_MW_MAX: update-list entries each workgroup found this step
-    MW_PEND = MW_SEGCNT + RCD_MW_MAX,            // RCD_KMAX x RCD_MW_MAX: segment lengths of block k's pending list
+    MW_SLOT = 16,                                // 2 banks x RCD_MW_MAX slots x 4 ints: a workgroup's post and its tag
+    MW_PEND = MW_SLOT + 2 * 4 * RCD_MW_MAX,      // RCD_KMAX x RCD_MW_MAX: segment lengths of block k's pending list
     MW_END = MW_PEND + RCD_KMAX * RCD_MW_MAX
 };
 static_assert(MW_END <= RCD_MW_INTS, "exchange area too small");
