@@ -34,11 +34,32 @@ __device__ __forceinline__ double *inc_gains(const RcdClass &st) { return reinte
 __device__ __forceinline__ float *inc_dold(const RcdClass &st) { return st.part + 2 * (size_t)st.K * st.ld; }
 __device__ __forceinline__ int32_t *inc_dlist(const RcdClass &st) { return reinterpret_cast<int32_t *>(st.gain); }
 
-// one term of the update, exact in double
+// One term of the update, in double: max(0, s - new) - max(0, s - old) with old < new, written as
+// -min(clamp(s - old, 0, 1), new - old) (s <= old: 0; old < s <= new: old - s; s > new: old - new; the upper
+// clamp never bites because the similarities lie in [0, 1]).  Every kernel of this route takes its terms from here,
+// so a gain is the same number whichever of them applied an update.
 __device__ __forceinline__ double inc_term(float s, float new_c, float old_c)
 {
-    const double d = (double)s;
-    return fmax(d - (double)new_c, 0.0) - fmax(d - (double)old_c, 0.0);
+    const double od = (double)old_c;
+    const double w = (double)new_c - od;
+    const double x = fmin(fmax((double)s - od, 0.0), 1.0);
+    return -fmin(x, w);
+}
+
+constexpr int INC_FUSE_MAX = 8;             // most blocks whose pending lists one fused update pass applies
+
+// Whether a class's pending lists are applied by rcd_k_inc_update_fused (one walk over the union of the lists'
+// rows) instead of list by list: two to eight blocks wait, the byte-per-sample membership table fits lds_bytes,
+// and the lists together hold at least pct percent of the class (then many rows are on several lists and the fused
+// pass reads such a row once).  Both update kernels evaluate this on the same descriptor, so exactly one of
+// them serves a class.  lds_bytes = 0 switches the fused pass off.
+__device__ __forceinline__ bool inc_fused(const RcdClass &st, int lds_bytes, int pct)
+{
+    const int nneed = st.nneed;
+    if (lds_bytes <= 0 || nneed < 2 || nneed > INC_FUSE_MAX || st.ld > lds_bytes) return false;
+    long long tot = 0;
+    for (int s = 0; s < nneed; ++s) tot += max(st.dcount[st.need[s]], 0);
+    return tot * 100 >= (long long)pct * st.n;
 }
 
 __device__ __forceinline__ double wave_sum_f64(double a)
@@ -76,11 +97,12 @@ rcd_k_inc_init(const RcdClass *__restrict__ classes)
 // read neighbouring kilobytes of the same rows at about the same time.
 // grid = (ceil(max ld / 1024), K, ncls).
 extern "C" __global__ void __launch_bounds__(256)
-rcd_k_inc_update(const RcdClass *__restrict__ classes)
+rcd_k_inc_update(const RcdClass *__restrict__ classes, int fuse_lds_bytes, int fuse_pct)
 {
     const RcdClass &st = classes[blockIdx.z];
     const int slot = blockIdx.y;
     if (st.done || slot >= st.nneed) return;
+    if (inc_fused(st, fuse_lds_bytes, fuse_pct)) return;      // the fused pass serves this class
     const int k = st.need[slot];
     const int ld = st.ld;
     const int lane = threadIdx.x & 63;
@@ -131,6 +153,150 @@ rcd_k_inc_update(const RcdClass *__restrict__ classes)
     double *g = inc_gains(st) + (size_t)k * ld + v0 + lane * 4;
 #pragma unroll
     for (int c = 0; c < 4; ++c) g[c] += acc[c];
+}
+
+namespace {
+
+__device__ __forceinline__ float inc_lane_value(float x, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+
+// U rows of one 64-row group (the lowest U set bits of `rows`, which has at least U): loads first, then every row's
+// terms for the blocks it is listed for.  mb: this lane's row's membership byte; cnv/cov: per block, this lane's row's
+// new and old coverage.
+template <int U>
+__device__ __forceinline__ void inc_fused_rows(unsigned long long &rows, unsigned mb, const float (&cnv)[INC_FUSE_MAX],
+                                               const float (&cov)[INC_FUSE_MAX], gcf32 Mj0, int ld,
+                                               double (&acc)[INC_FUSE_MAX][4])
+{
+    int bit[U];
+    unsigned mk[U];
+    f32x4 m[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        bit[u] = (int)__builtin_ctzll(rows);
+        rows &= rows - 1ull;
+        mk[u] = (unsigned)__builtin_amdgcn_readlane((int)mb, bit[u]);
+        m[u] = __builtin_nontemporal_load((gcf32x4)(Mj0 + (size_t)bit[u] * ld));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int s = 0; s < INC_FUSE_MAX; ++s) {
+            if ((mk[u] >> s) & 1u) {
+                const float cn = inc_lane_value(cnv[s], bit[u]), co = inc_lane_value(cov[s], bit[u]);
+                acc[s][0] += inc_term(m[u].x, cn, co);
+                acc[s][1] += inc_term(m[u].y, cn, co);
+                acc[s][2] += inc_term(m[u].z, cn, co);
+                acc[s][3] += inc_term(m[u].w, cn, co);
+            }
+        }
+    }
+}
+
+} // namespace
+
+// The same update for a class whose pending lists overlap (inc_fused above): one walk over the samples j in
+// ascending order, a row of S read once and its terms added to every block that lists j.  A block's gains
+// receive the same terms in the same order as from rcd_k_inc_update, hence the same bits.
+// The workgroup first marks, in a table of one byte per sample in LDS, which blocks list which j (bit s: block
+// need[s]); then each of its 4 waves takes 256 samples v and walks the table 64 rows at a time: the group's
+// coverage values (new from cur, old from the lists, whose entries are met in list order) are fetched one row
+// per lane, the listed rows are read eight at a time.
+// plans[1].fused counts the classes served.
+// grid = (ceil(max ld / 1024), ncls), dynamic LDS = lds_bytes >= ld of every class served.
+extern "C" __global__ void __launch_bounds__(256)
+rcd_k_inc_update_fused(const RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int lds_bytes, int pct)
+{
+    extern __shared__ unsigned int inc_member[];
+    const RcdClass &st = classes[blockIdx.y];
+    if (st.done || !inc_fused(st, lds_bytes, pct)) return;
+    const int ld = st.ld;
+    if ((int)blockIdx.x * 1024 >= ld) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the host stops launching this kernel once a batch of rounds has gone by without a class for it
+    if (blockIdx.x == 0 && tid == 0) __hip_atomic_fetch_add(&plans[1].fused, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int nneed = st.nneed;
+    const bool shared = st.mw > 1;
+    const int nseg = shared ? st.mw : 1;
+    const int seg_len = shared ? st.mwseg : ld;      // a list's segment sg holds the changed j of [sg seg_len, (sg+1) seg_len)
+    for (int i = tid; i < ld / 4; i += 256) inc_member[i] = 0u;
+    __syncthreads();
+    for (int s = 0; s < nneed; ++s) {
+        const int k = st.need[s];
+        for (int sg = 0; sg < nseg; ++sg) {
+            const int nd = shared ? st.mwbuf[MW_PEND + k * RCD_MW_MAX + sg] : st.dcount[k];
+            const cci32 dl = (cci32)(inc_dlist(st) + (size_t)k * ld + (shared ? (size_t)sg * seg_len : 0));
+            for (int e = tid; e < nd; e += 256) {
+                const int j = dl[e];
+                atomicOr(&inc_member[j >> 2], (1u << s) << ((j & 3) * 8));
+            }
+        }
+    }
+    __syncthreads();
+    const int v0 = blockIdx.x * 1024 + wave * 256;
+    if (v0 >= ld) return;
+
+    const unsigned char *member = reinterpret_cast<const unsigned char *>(inc_member);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const gcf32 M = (gcf32)st.M + v0 + lane * 4;
+    // per block: coverage vector, the list's old values, position in the list (slots past nneed repeat the last
+    // block; their bit is never set)
+    ccf32 curp[INC_FUSE_MAX], oldp[INC_FUSE_MAX];
+    int pos[INC_FUSE_MAX];
+#pragma unroll
+    for (int s = 0; s < INC_FUSE_MAX; ++s) {
+        const int k = st.need[min(s, nneed - 1)];
+        curp[s] = (ccf32)(st.cur + (size_t)k * ld);
+        oldp[s] = (ccf32)(inc_dold(st) + (size_t)k * ld);
+        pos[s] = 0;
+    }
+    double acc[INC_FUSE_MAX][4];
+#pragma unroll
+    for (int s = 0; s < INC_FUSE_MAX; ++s)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[s][c] = 0.0;
+
+    int next_seg = 0;
+    for (int j0 = 0; j0 < ld; j0 += 64) {
+        if (j0 == next_seg) {        // a new segment of every list starts at the offset of its slice
+#pragma unroll
+            for (int s = 0; s < INC_FUSE_MAX; ++s) pos[s] = shared ? j0 : 0;
+            next_seg += seg_len;
+        }
+        const unsigned mb = member[j0 + lane];
+        unsigned long long rows = __ballot(mb != 0u);
+        if (rows == 0ull) continue;
+        float cnv[INC_FUSE_MAX], cov[INC_FUSE_MAX];
+#pragma unroll
+        for (int s = 0; s < INC_FUSE_MAX; ++s) {
+            const bool in = (mb >> s) & 1u;
+            const unsigned long long bs = __ballot(in);
+            const int e = pos[s] + __popcll(bs & below);
+            cnv[s] = 0.0f;
+            cov[s] = 0.0f;
+            if (in) {
+                cnv[s] = curp[s][j0 + lane];
+                cov[s] = oldp[s][e];
+            }
+            pos[s] += __popcll(bs);
+        }
+        const gcf32 Mj0 = M + (size_t)j0 * ld;
+        while (__popcll(rows) >= 8) inc_fused_rows<8>(rows, mb, cnv, cov, Mj0, ld, acc);
+        if (__popcll(rows) >= 4) inc_fused_rows<4>(rows, mb, cnv, cov, Mj0, ld, acc);
+        if (__popcll(rows) >= 2) inc_fused_rows<2>(rows, mb, cnv, cov, Mj0, ld, acc);
+        if (rows != 0ull) inc_fused_rows<1>(rows, mb, cnv, cov, Mj0, ld, acc);
+    }
+#pragma unroll
+    for (int s = 0; s < INC_FUSE_MAX; ++s) {
+        if (s < nneed) {
+            double *g = inc_gains(st) + (size_t)st.need[s] * ld + v0 + lane * 4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) g[c] += acc[s][c];
+        }
+    }
 }
 
 namespace {

@@ -242,6 +242,8 @@ int sweep_setup()
         HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rcd_k_sweep_rows),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, RCD_SWEEP_LDS_FLOATS * 4));
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rcd_k_inc_update_fused),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, RCD_INC_FUSE_LDS_MAX));
         ds->cus = std::max(cus, 1);
     }
     return RCD_OK;
@@ -374,6 +376,9 @@ struct Lane {
     long long mw_spin_ticks = 200000000;   // bound of a grid-barrier wait, 100 MHz ticks (2 s)
     dim3 update_grid;
     int inc_small_bytes = 512 << 10;   // update lists up to this many bytes of rows are applied by the step loop itself
+    int inc_fuse_lds = 0;              // LDS bytes of the fused update pass (its membership table); 0: no fused pass
+    int inc_fuse_pct = 50;             // a class's lists are fused when together they hold this share of its samples
+    int inc_fuse_seen = -1;            // plans[1].fused as of the last batch read back
     int inc_max_steps = 64;     // steps per class and launch: a class that waits for the update launch waits for the whole lane
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
     size_t round_rc_lds = 0;   // dynamic LDS of the recompute sweep (fast path only)
@@ -526,6 +531,16 @@ struct Lane {
             int max_ld = 0;
             for (const RcdClass &c : g->host) max_ld = std::max(max_ld, c.ld);
             update_grid = dim3((unsigned)((max_ld + 1023) / 1024), (unsigned)first.K, (unsigned)ncls);
+            // Large classes: while the pending lists of a class overlap (the first rounds), one fused pass applies them
+            // all.  Its table of one byte per sample must fit beside nothing else in LDS.
+            const int fuse_min_n = env_int("RCD_INC_FUSE_MIN_N", 16384, 0, 1 << 30);
+            inc_fuse_pct = env_int("RCD_INC_FUSE_PCT", 50, 1, 1000);
+            inc_fuse_lds = 0;
+            inc_fuse_seen = -1;
+            if (fuse_min_n > 0 && max_n >= fuse_min_n && max_ld <= RCD_INC_FUSE_LDS_MAX) {
+                RCD_TRY(sweep_setup());          // raises that kernel's LDS limit
+                inc_fuse_lds = (max_ld + 1023) / 1024 * 1024;
+            }
             // initial gains = column sums of S: every coverage vector is 0
             hipLaunchKernelGGL(rcd_k_inc_init, dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls), dim3(256), 0, stream,
                                (const RcdClass *)g->classes_dev);
@@ -602,7 +617,14 @@ struct Lane {
                 hipLaunchKernelGGL(round_rc, dim3(items_ub), dim3(256), round_rc_lds, stream, g->classes_dev, g->plan_dev,
                                    buf);
             else if (incremental)
-                hipLaunchKernelGGL(rcd_k_inc_update, update_grid, dim3(256), 0, stream, (const RcdClass *)g->classes_dev);
+            {
+                hipLaunchKernelGGL(rcd_k_inc_update, update_grid, dim3(256), 0, stream, (const RcdClass *)g->classes_dev,
+                                   inc_fuse_lds, inc_fuse_pct);
+                if (inc_fuse_lds > 0)
+                    hipLaunchKernelGGL(rcd_k_inc_update_fused, dim3(update_grid.x, update_grid.z), dim3(256),
+                                       (size_t)inc_fuse_lds, stream, (const RcdClass *)g->classes_dev, g->plan_dev,
+                                       inc_fuse_lds, inc_fuse_pct);
+            }
             else
                 hipLaunchKernelGGL(rcd_k_sweep_rows, dim3(sweep_wgs), dim3(RCD_SWEEP_THREADS),
                                    RCD_SWEEP_LDS_FLOATS * 4, stream, (const RcdClass *)g->classes_dev,
@@ -665,6 +687,12 @@ struct Lane {
         }
         if (seen[0].bad) { finished = true; return RCD_ERR_BAD_SIMILARITY; }
         if (std::max(seen[0].ndone, seen[1].ndone) >= ncls) finished = true;
+        if (inc_fuse_lds > 0) {
+            // the lists overlap in a run's first rounds only: after a batch in which no class took the fused pass the
+            // launches to come leave it out (both update kernels get the same switch, so either serves a class)
+            if (seen[1].fused == inc_fuse_seen) inc_fuse_lds = 0;
+            inc_fuse_seen = seen[1].fused;
+        }
         return RCD_OK;
     }
 

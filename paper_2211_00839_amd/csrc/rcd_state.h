@@ -16,6 +16,7 @@
 #define RCD_CMAX 32          // most row chunks a class's sweep is split into
 #define RCD_SWEEP_WAVES 16    // waves of a stored-S sweep workgroup: each streams one candidate row at a time
 #define RCD_SWEEP_THREADS (64 * RCD_SWEEP_WAVES)
+#define RCD_INC_FUSE_LDS_MAX (152 * 1024)   // most LDS the fused update pass of the incremental route may take (a byte per sample)
 #define RCD_SWEEP_LDS_FLOATS 32768   // LDS of a stored-S sweep workgroup: coverage of the evaluated blocks, one chunk of j
 #define RCD_STEP_THREADS 1024
 #define RCD_MW_MAX 32        // most workgroups that share one class in the multi-workgroup step loops
@@ -101,7 +102,8 @@ struct RcdPlan {
     int32_t nactive;     // classes with work this round
     int32_t ndone;       // classes finished
     int32_t bad;         // set by validation kernels (buffer 0 only)
-    int32_t pad[2];
+    int32_t fused;       // incremental route: classes served by the fused update pass so far (buffer 1's copy counts)
+    int32_t pad;
 };
 
 // Stored-S sweep: which class a workgroup serves, and as which of how many.
