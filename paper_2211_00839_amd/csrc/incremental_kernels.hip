@@ -205,27 +205,31 @@ __device__ __forceinline__ void inc_fused_rows(unsigned long long &rows, unsigne
 // coverage values (new from cur, old from the lists, whose entries are met in list order) are fetched one row
 // per lane, the listed rows are read eight at a time.
 // plans[1].fused counts the classes served.
-// grid = (ceil(max ld / 1024), ncls), dynamic LDS = lds_bytes >= ld of every class served.
+// grid = (ceil(max ld / 1024), ceil(min(K, 8) / per_wg), ncls), dynamic LDS = lds_bytes >= ld of every class served.
 extern "C" __global__ void __launch_bounds__(256)
-rcd_k_inc_update_fused(const RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int lds_bytes, int pct)
+rcd_k_inc_update_fused(const RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int lds_bytes, int pct,
+                       int per_wg)
 {
     extern __shared__ unsigned int inc_member[];
-    const RcdClass &st = classes[blockIdx.y];
+    const RcdClass &st = classes[blockIdx.z];
     if (st.done || !inc_fused(st, lds_bytes, pct)) return;
     const int ld = st.ld;
-    if ((int)blockIdx.x * 1024 >= ld) return;
+    // this workgroup's share of the waiting blocks: need[s_base .. s_base + nmine)
+    const int s_base = blockIdx.y * per_wg;
+    const int nmine = min(per_wg, st.nneed - s_base);
+    if ((int)blockIdx.x * 1024 >= ld || nmine <= 0) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // the host stops launching this kernel once a batch of rounds has gone by without a class for it
-    if (blockIdx.x == 0 && tid == 0) __hip_atomic_fetch_add(&plans[1].fused, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int nneed = st.nneed;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0)
+        __hip_atomic_fetch_add(&plans[1].fused, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const bool shared = st.mw > 1;
     const int nseg = shared ? st.mw : 1;
     const int seg_len = shared ? st.mwseg : ld;      // a list's segment sg holds the changed j of [sg seg_len, (sg+1) seg_len)
     for (int i = tid; i < ld / 4; i += 256) inc_member[i] = 0u;
     __syncthreads();
-    for (int s = 0; s < nneed; ++s) {
-        const int k = st.need[s];
+    for (int s = 0; s < nmine; ++s) {
+        const int k = st.need[s_base + s];
         for (int sg = 0; sg < nseg; ++sg) {
             const int nd = shared ? st.mwbuf[MW_PEND + k * RCD_MW_MAX + sg] : st.dcount[k];
             const cci32 dl = (cci32)(inc_dlist(st) + (size_t)k * ld + (shared ? (size_t)sg * seg_len : 0));
@@ -242,13 +246,13 @@ rcd_k_inc_update_fused(const RcdClass *__restrict__ classes, RcdPlan *__restrict
     const unsigned char *member = reinterpret_cast<const unsigned char *>(inc_member);
     const unsigned long long below = (1ull << lane) - 1ull;
     const gcf32 M = (gcf32)st.M + v0 + lane * 4;
-    // per block: coverage vector, the list's old values, position in the list (slots past nneed repeat the last
+    // per block: coverage vector, the list's old values, position in the list (slots past nmine repeat the last
     // block; their bit is never set)
     ccf32 curp[INC_FUSE_MAX], oldp[INC_FUSE_MAX];
     int pos[INC_FUSE_MAX];
 #pragma unroll
     for (int s = 0; s < INC_FUSE_MAX; ++s) {
-        const int k = st.need[min(s, nneed - 1)];
+        const int k = st.need[s_base + min(s, nmine - 1)];
         curp[s] = (ccf32)(st.cur + (size_t)k * ld);
         oldp[s] = (ccf32)(inc_dold(st) + (size_t)k * ld);
         pos[s] = 0;
@@ -291,8 +295,8 @@ rcd_k_inc_update_fused(const RcdClass *__restrict__ classes, RcdPlan *__restrict
     }
 #pragma unroll
     for (int s = 0; s < INC_FUSE_MAX; ++s) {
-        if (s < nneed) {
-            double *g = inc_gains(st) + (size_t)st.need[s] * ld + v0 + lane * 4;
+        if (s < nmine) {
+            double *g = inc_gains(st) + (size_t)st.need[s_base + s] * ld + v0 + lane * 4;
 #pragma unroll
             for (int c = 0; c < 4; ++c) g[c] += acc[s][c];
         }

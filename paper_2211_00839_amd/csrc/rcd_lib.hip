@@ -379,6 +379,7 @@ struct Lane {
     int inc_fuse_lds = 0;              // LDS bytes of the fused update pass (its membership table); 0: no fused pass
     int inc_fuse_pct = 50;             // a class's lists are fused when together they hold this share of its samples
     int inc_fuse_seen = -1;            // plans[1].fused as of the last batch read back
+    int inc_fuse_per_wg = 8;           // waiting blocks a workgroup of the fused pass serves
     int inc_max_steps = 64;     // steps per class and launch: a class that waits for the update launch waits for the whole lane
     void (*round_rc)(RcdClass *, RcdPlan *, int) = nullptr;
     size_t round_rc_lds = 0;   // dynamic LDS of the recompute sweep (fast path only)
@@ -537,9 +538,16 @@ struct Lane {
             inc_fuse_pct = env_int("RCD_INC_FUSE_PCT", 50, 1, 1000);
             inc_fuse_lds = 0;
             inc_fuse_seen = -1;
-            if (fuse_min_n > 0 && max_n >= fuse_min_n && max_ld <= RCD_INC_FUSE_LDS_MAX) {
+            if (fuse_min_n > 0 && max_n >= fuse_min_n && max_ld <= RCD_INC_FUSE_LDS_MAX && first.K >= 2) {
                 RCD_TRY(sweep_setup());          // raises that kernel's LDS limit
-                inc_fuse_lds = (max_ld + 1023) / 1024 * 1024;
+                // A workgroup serves a tile of 1024 samples and up to eight waiting blocks.  With few classes that is too
+                // few workgroups for the device (one class of 50 000: 49), so the blocks are dealt to several then, down
+                // to two each; one block each is the list-by-list kernel's job.
+                const int slots = std::min(first.K, 8);
+                const int64_t tiles = (int64_t)update_grid.x * ncls;
+                const int groups = (int)std::min<int64_t>(slots, std::max<int64_t>(1, (3 * (int64_t)cu_count() + tiles - 1) / tiles));
+                inc_fuse_per_wg = env_int("RCD_INC_FUSE_BLOCKS", (slots + groups - 1) / groups, 1, 8);
+                if (inc_fuse_per_wg >= 2) inc_fuse_lds = (max_ld + 1023) / 1024 * 1024;
             }
             // initial gains = column sums of S: every coverage vector is 0
             hipLaunchKernelGGL(rcd_k_inc_init, dim3((unsigned)((max_n + 3) / 4), (unsigned)ncls), dim3(256), 0, stream,
@@ -621,9 +629,11 @@ struct Lane {
                 hipLaunchKernelGGL(rcd_k_inc_update, update_grid, dim3(256), 0, stream, (const RcdClass *)g->classes_dev,
                                    inc_fuse_lds, inc_fuse_pct);
                 if (inc_fuse_lds > 0)
-                    hipLaunchKernelGGL(rcd_k_inc_update_fused, dim3(update_grid.x, update_grid.z), dim3(256),
-                                       (size_t)inc_fuse_lds, stream, (const RcdClass *)g->classes_dev, g->plan_dev,
-                                       inc_fuse_lds, inc_fuse_pct);
+                    hipLaunchKernelGGL(rcd_k_inc_update_fused,
+                                       dim3(update_grid.x, (unsigned)((std::min(g->K, 8) + inc_fuse_per_wg - 1) / inc_fuse_per_wg),
+                                            update_grid.z),
+                                       dim3(256), (size_t)inc_fuse_lds, stream, (const RcdClass *)g->classes_dev,
+                                       g->plan_dev, inc_fuse_lds, inc_fuse_pct, inc_fuse_per_wg);
             }
             else
                 hipLaunchKernelGGL(rcd_k_sweep_rows, dim3(sweep_wgs), dim3(RCD_SWEEP_THREADS),

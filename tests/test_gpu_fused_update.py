@@ -33,8 +33,9 @@ def mixture_S(seed, n, d=16):
     return oracle.similarity(si.make_class(seed=seed, n=n, d=d), float(d))
 
 
-def run(rcd, monkeypatch, S, cap, fused, pct=50, shared=False, small_kb=None):
+def run(rcd, monkeypatch, S, cap, fused, pct=50, shared=False, small_kb=None, blocks=8):
     monkeypatch.setenv("RCD_INC_FUSE_MIN_N", "1" if fused else "0")
+    monkeypatch.setenv("RCD_INC_FUSE_BLOCKS", str(blocks))     # waiting blocks per workgroup of the fused pass
     monkeypatch.setenv("RCD_INC_FUSE_PCT", str(pct))
     monkeypatch.setenv("RCD_MW_MIN_N", "1" if shared else "0")
     monkeypatch.setenv("RCD_MW_SLICE", "256")
@@ -46,14 +47,16 @@ def run(rcd, monkeypatch, S, cap, fused, pct=50, shared=False, small_kb=None):
 
 
 @pytest.mark.parametrize("shared", [False, True])
-@pytest.mark.parametrize("n,r,pct", [(1500, [1, 1, 2, 4], 50), (2100, [1, 1, 1, 2, 2, 3, 4, 6], 50), (2100, [1, 1, 1, 2, 2, 3, 4, 6], 1),
-                                     (1000, [3, 1, 4, 1, 2, 2, 1, 3, 4, 4, 1, 2], 1), (257, [5, 5], 1), (3000, [1, 2, 3], 10)])
-def test_fused_pass_gives_the_list_by_list_bits(rcd, monkeypatch, shared, n, r, pct):
-    print(f"fused update: n={n} K={len(r)} pct={pct} shared={shared}", flush=True)
+@pytest.mark.parametrize("n,r,pct,blocks", [(1500, [1, 1, 2, 4], 50, 8), (2100, [1, 1, 1, 2, 2, 3, 4, 6], 50, 8),
+                                            (2100, [1, 1, 1, 2, 2, 3, 4, 6], 1, 3), (2100, [1, 1, 1, 2, 2, 3, 4, 6], 30, 2),
+                                            (1000, [3, 1, 4, 1, 2, 2, 1, 3, 4, 4, 1, 2], 1, 4), (257, [5, 5], 1, 8),
+                                            (3000, [1, 2, 3], 10, 2)])
+def test_fused_pass_gives_the_list_by_list_bits(rcd, monkeypatch, shared, n, r, pct, blocks):
+    print(f"fused update: n={n} K={len(r)} pct={pct} blocks per workgroup={blocks} shared={shared}", flush=True)
     S = mixture_S(500 + n, n)
     cap = oracle.quota(n, r)
     # lists of more than one row go to the update launches, so that the fused pass sees sparse lists too
-    a1, o1, f1, _ = run(rcd, monkeypatch, S, cap, fused=True, pct=pct, shared=shared, small_kb=1)
+    a1, o1, f1, _ = run(rcd, monkeypatch, S, cap, fused=True, pct=pct, shared=shared, small_kb=1, blocks=blocks)
     a0, o0, f0, _ = run(rcd, monkeypatch, S, cap, fused=False, shared=shared, small_kb=1)
     assert np.array_equal(a1, a0) and np.array_equal(o1, o0) and np.array_equal(f1, f0)
     res = oracle.lockstep(S, cap, o1, a1, rel_tol=1e-5, objective="fl")
@@ -85,6 +88,7 @@ def test_data_set_with_fused_and_unfused_classes(rcd, monkeypatch):
     # classes of very different sizes in one launch: every class decides by itself, launch by launch
     monkeypatch.setenv("RCD_INC_FUSE_MIN_N", "1")
     monkeypatch.setenv("RCD_INC_FUSE_PCT", "20")
+    monkeypatch.setenv("RCD_INC_FUSE_BLOCKS", "3")
     monkeypatch.setenv("RCD_INC_SMALL_KB", "1")
     monkeypatch.setenv("RCD_MW_MIN_N", "1")
     monkeypatch.setenv("RCD_MW_SLICE", "512")
