@@ -605,7 +605,8 @@ gram_rbf_fast_tile(const T *__restrict__ X, long long ldx, const int32_t *__rest
     const long long step1 = lds_out, step5 = 5 * lds_out;
     // EPI_RBF_MIRROR: a tile above the diagonal also writes its transpose, S(j,i) = S(i,j).  A lane's four
     // consecutive rows of one column are four consecutive floats of the mirrored row; stored straight
-    // from the registers they would leave as 16-byte pieces of 32 different lines per instruction.  An
+    // from the registers they leave as 16-byte pieces of 32 different lines per instruction (measured: the
+    // 50 000 x 2048 build takes 9.1 ms that way against 5.6 ms).  An
     // interior tile therefore turns each 32-row band of a wave's sub-tile round in LDS (the ring is
     // idle; a wave has a region of its own, 128 mirrored rows of 32 floats at a pitch of 36) and stores
     // it as whole 128-byte lines, eight per instruction.  Edge tiles store element by element, checked.
