@@ -28,6 +28,14 @@
  *     anything else runs.  No exception or abort crosses the boundary.
  *   - Same inputs give byte-identical outputs (fixed reduction orders, no
  *     floating-point atomics).
+ *   - Tuning: the partition and similarity calls read a few environment
+ *     variables named RCD_* at each call (lanes, rounds per batch, workgroups
+ *     per launch, steps per launch, the sizes from which large classes are
+ *     shared among workgroups or their update lists fused, the bound of a
+ *     wait between those workgroups).  They set launch shapes and thresholds
+ *     only: none selects the algorithmic route (that is the `mode` argument),
+ *     and every setting meets the contract stated at the entry point.  Unset,
+ *     each has a measured default.
  *   - "lowest index" always means the lowest position in the caller's arrays.
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
  */
