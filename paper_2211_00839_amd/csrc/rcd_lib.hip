@@ -517,6 +517,10 @@ struct Lane {
                     // a shared class steps about four times faster: four times the steps per call for the same wait
                     if (ncls > 1)
                         inc_max_steps = env_int("RCD_INC_STEPS", std::min(64, std::max(8, 1600000 / std::max(max_n, 1))), 1, 1 << 20);
+                    // with many classes in the launch an update launch gives each class a small share of the memory
+                    // bandwidth, and lists four times as long are better applied by the class's own workgroups
+                    // (20 classes of 50 000: 1.92 -> 1.86 s; one class alone: 774 -> 875 ms, so not there)
+                    if (ncls >= 4) inc_small_bytes = env_int("RCD_INC_SMALL_KB", 2048, 1, 1 << 20) * 1024;
                     HIP_TRY(hipMemcpyAsync(g->wgmap_dev, map.data(), sizeof(RcdWg) * map.size(), hipMemcpyHostToDevice, stream));
                     HIP_TRY(hipMemcpyAsync(g->classes_dev, g->host.data(), sizeof(RcdClass) * ncls, hipMemcpyHostToDevice, stream));
                 } else {
