@@ -84,11 +84,13 @@ __device__ __forceinline__ void dev_store4i(int32_t *p, int a, int b, int c, int
 }
 
 // Every thread of the workgroup calls this with the same (a, b, c).  On return ms.a/b/c[0..W) hold the posts.
-__device__ __forceinline__ bool mw_exchange(MwExchange &x, MwShared &ms, int a, int b, int c)
+// publish: the workgroup has written memory that the others read after this exchange (its list segment); the
+// post then waits for those stores.  Everything else a step writes is read back by the writing workgroup only.
+__device__ __forceinline__ bool mw_exchange(MwExchange &x, MwShared &ms, int a, int b, int c, bool publish)
 {
     const int tid = threadIdx.x;
-    wait_for_my_stores();      // what I wrote for the others has left this compute unit ...
-    __syncthreads();           // ... and so has what the rest of my workgroup wrote
+    if (publish) wait_for_my_stores();      // what I wrote for the others has left this compute unit ...
+    __syncthreads();                        // ... and so has what the rest of my workgroup wrote
     x.epoch += 1;
     if (x.W == 1) {
         if (tid == 0) { ms.a[0] = a; ms.b[0] = b; ms.c[0] = c; ms.ok = 1; }
@@ -125,7 +127,7 @@ __device__ __forceinline__ bool mw_exchange(MwExchange &x, MwShared &ms, int a, 
 __device__ __forceinline__ bool mw_best_of_class(MwExchange &x, MwShared &ms, unsigned long long &key, int &bv)
 {
     if (x.W == 1) return true;
-    if (!mw_exchange(x, ms, (int)(unsigned)(key >> 32), (int)(unsigned)key, bv)) return false;
+    if (!mw_exchange(x, ms, (int)(unsigned)(key >> 32), (int)(unsigned)key, bv, false)) return false;
     key = ((unsigned long long)(unsigned)ms.a[0] << 32) | (unsigned)ms.b[0];
     bv = ms.c[0];
     for (int i = 1; i < x.W; ++i)
@@ -170,7 +172,7 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
     bar.epoch = epoch0;
     bar.deadline = tick0 + spin_ticks;
     // everyone holds its copy of the descriptor before anyone may write it back
-    if (!mw_exchange(bar, ms, 0, 0, 0)) return;
+    if (!mw_exchange(bar, ms, 0, 0, 0, false)) return;
 
     const int K = d.K, n = d.n, ld = d.ld, total = d.total;
     if (tid < d.nneed) d.valid[d.need[tid]] = 1;      // the update launch brought these blocks' gains up to date
@@ -322,7 +324,7 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
             }
         }
         // ---- the whole list: every workgroup's segment, in order (the exchange carries the segment lengths)
-        if (!mw_exchange(bar, ms, mine, 0, 0)) { alive = false; break; }
+        if (!mw_exchange(bar, ms, mine, 0, 0, mine > 0)) { alive = false; break; }
         int nd = 0;
         for (int i = 0; i < W; ++i) nd += ms.a[i];
         entries += (long long)nd * n;
@@ -460,7 +462,7 @@ rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, c
     bar.w = w;
     bar.epoch = epoch0;
     bar.deadline = tick0 + spin_ticks;
-    if (!mw_exchange(bar, ms, 0, 0, 0)) return;
+    if (!mw_exchange(bar, ms, 0, 0, 0, false)) return;
 
     const int K = d.K, n = d.n, ld = d.ld, total = d.total;
     double *G = inc_gains(d);
