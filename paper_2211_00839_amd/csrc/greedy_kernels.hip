@@ -633,6 +633,27 @@ __device__ __forceinline__ void wave_best(unsigned long long &key, int &pos)
     key = ((unsigned long long)mhi << 32) | mlo;
 }
 
+// Algorithm 1's choice of the block: the non-full block of least f, lowest index on ties; -1 when every block is
+// full.  d lives in LDS.  Lane k looks at block k (the lanes past RCD_KMAX repeat them), so the choice costs one
+// trip to LDS and two wave reductions instead of a chain of K dependent reads; the result is the same in every
+// lane and sits in a scalar register.  The least f is found as the largest order-preserving key of -f (-0 made +0).
+__device__ __forceinline__ int least_open_block(const RcdClass &d, int K)
+{
+    static_assert((RCD_KMAX & (RCD_KMAX - 1)) == 0 && RCD_KMAX <= 64, "a lane per block");
+    const int k = (int)(threadIdx.x & (RCD_KMAX - 1));
+    const bool open = k < K && d.cnt[k] < d.cap[k];
+    unsigned long long key = 0ull;               // below the key of any number
+    if (open) {
+        const unsigned long long b = (unsigned long long)__double_as_longlong(-d.f[k] + 0.0);
+        key = (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+    }
+    const unsigned hi = (unsigned)(key >> 32), lo = (unsigned)key;
+    const unsigned mhi = wave_max_u32(hi);
+    const unsigned mlo = wave_max_u32(hi == mhi ? lo : 0u);
+    const unsigned long long who = __ballot(open && hi == mhi && lo == mlo);
+    return who ? ((__ffsll((long long)who) - 1) & (RCD_KMAX - 1)) : -1;
+}
+
 template <int NT>
 __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsShared &sh)
 {
@@ -796,15 +817,8 @@ __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsSha
     long long useful = 0;
     for (;;) {
         if (t >= total) { done = 1; break; }
-        int js = -1;
-        double fbest = 0.0;
-        for (int k = 0; k < K; ++k) {
-            if (d.cnt[k] >= d.cap[k]) continue;
-            const double fk = d.f[k];
-            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
-        }
+        const int js = least_open_block(d, K);
         if (js < 0) { done = 1; break; }
-        js = uni(js);
         if (!d.valid[js]) break;
         const int nrem = uni(sh.nrem);
         int pstar = sh.bpos[js];

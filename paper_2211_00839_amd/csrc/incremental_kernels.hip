@@ -419,13 +419,7 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
     for (;;) {
         if (t >= total) { done = 1; break; }
         if (t - t0 >= max_steps) break;      // a class that waits for the update launch waits for every class's call
-        int js = -1;
-        double fbest = 0.0;
-        for (int k = 0; k < K; ++k) {
-            if (d.cnt[k] >= d.cap[k]) continue;
-            const double fk = d.f[k];
-            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
-        }
+        const int js = least_open_block(d, K);
         if (js < 0) { done = 1; break; }
         if (!d.valid[js]) break;
 
@@ -658,13 +652,7 @@ rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
     for (;;) {
         if (t >= total) { done = 1; break; }
         if (t - t0 >= max_steps) break;
-        int js = -1;
-        double fbest = 0.0;
-        for (int k = 0; k < K; ++k) {
-            if (d.cnt[k] >= d.cap[k]) continue;
-            const double fk = d.f[k];
-            if (js < 0 || fk < fbest) { js = k; fbest = fk; }
-        }
+        const int js = least_open_block(d, K);
         if (js < 0) { done = 1; break; }
         // ---- argmax over the block's marginal values (they may be negative)
         double *g = G + (size_t)js * ld;
