@@ -441,12 +441,13 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
         if (vstar >= n) { done = 1; break; }          // no candidate left (cannot happen while t < total <= n)
 
         // ---- bookkeeping and outputs
+        // (where v* goes in the caller's arrays is asked for now and used at the end of the step: the answer is a
+        // trip to memory that the first wave would otherwise sit out before its share of the coverage update)
+        int oi = vstar;
         if (tid == 0) {
             d.cnt[js] += 1;
             d.f[js] += best;
-            const int oi = d.out_index ? d.out_index[vstar] : vstar;
-            d.assign_out[oi] = js;
-            if (d.order_out) d.order_out[oi] = t;
+            if (d.out_index) oi = d.out_index[vstar];
         }
         if (tid < K) G[(size_t)tid * ld + vstar] = INC_TAKEN;
 
@@ -557,6 +558,10 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
 #pragma unroll
                 for (int c = 0; c < 4; ++c) gj[v0 + c] += acc[c];
             }
+        }
+        if (tid == 0) {
+            d.assign_out[oi] = js;
+            if (d.order_out) d.order_out[oi] = t;
         }
         useful += nR;
         nR -= 1;
@@ -671,12 +676,11 @@ rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }
         // (every thread chose js from the block state before the barrier above: it may change now)
+        int oi = vstar;              // asked for now, used at the end of the step (see rcd_k_inc_steps)
         if (tid == 0) {
             d.cnt[js] += 1;
             d.f[js] += best;
-            const int oi = d.out_index ? d.out_index[vstar] : vstar;
-            d.assign_out[oi] = js;
-            if (d.order_out) d.order_out[oi] = t;
+            if (d.out_index) oi = d.out_index[vstar];
         }
         // ---- every marginal value of the block drops by 2 S(v, v*); v* leaves every block's candidates
         const gcf32 row = M + (size_t)vstar * ld;
@@ -708,6 +712,10 @@ rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
         // entry strikes it out (its own earlier store to the same address: no barrier in between is needed)
         if ((vstar >> 2) % NT == tid) g[vstar] = INC_TAKEN;
         if (tid < K && tid != js) G[(size_t)tid * ld + vstar] = INC_TAKEN;
+        if (tid == 0) {
+            d.assign_out[oi] = js;
+            if (d.order_out) d.order_out[oi] = t;
+        }
         useful += nR;
         nR -= 1;
         ++t;

@@ -222,14 +222,11 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
 
         // ---- bookkeeping (every workgroup keeps the same copy of the state) and outputs (workgroup 0)
         __syncthreads();                              // everyone has read the block state this step was decided on
+        int oi = vstar;              // asked for now, used at the end of the step (see rcd_k_inc_steps)
         if (tid == 0) {
             d.cnt[js] += 1;
             d.f[js] += best;
-            if (w == 0) {
-                const int oi = d.out_index ? d.out_index[vstar] : vstar;
-                d.assign_out[oi] = js;
-                if (d.order_out) d.order_out[oi] = t;
-            }
+            if (w == 0 && d.out_index) oi = d.out_index[vstar];
         }
         if (tid < K && vstar >= v0 && vstar < v1) G[(size_t)tid * ld + vstar] = INC_TAKEN;
 
@@ -389,6 +386,10 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
                 }
             }
         }
+        if (tid == 0 && w == 0) {
+            d.assign_out[oi] = js;
+            if (d.order_out) d.order_out[oi] = t;
+        }
         useful += nR;
         nR -= 1;
         ++t;
@@ -490,14 +491,11 @@ rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, c
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }
         __syncthreads();                              // everyone has read the block state this step was decided on
+        int oi = vstar;              // asked for now, used at the end of the step (see rcd_k_inc_steps)
         if (tid == 0) {
             d.cnt[js] += 1;
             d.f[js] += best;
-            if (w == 0) {
-                const int oi = d.out_index ? d.out_index[vstar] : vstar;
-                d.assign_out[oi] = js;
-                if (d.order_out) d.order_out[oi] = t;
-            }
+            if (w == 0 && d.out_index) oi = d.out_index[vstar];
         }
         // ---- every marginal value of the block drops by 2 S(v, v*), on my slice
         const gcf32 row = M + (size_t)vstar * ld;
@@ -531,6 +529,10 @@ rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, c
         if (vstar >= v0 && vstar < v1) {
             if (((vstar - v0) >> 2) % NT == tid) g[vstar] = INC_TAKEN;
             if (tid < K && tid != js) G[(size_t)tid * ld + vstar] = INC_TAKEN;
+        }
+        if (tid == 0 && w == 0) {
+            d.assign_out[oi] = js;
+            if (d.order_out) d.order_out[oi] = t;
         }
         useful += nR;
         nR -= 1;
