@@ -20,7 +20,7 @@
 #define RCD_SWEEP_LDS_FLOATS 32768   // LDS of a stored-S sweep workgroup: coverage of the evaluated blocks, one chunk of j
 #define RCD_STEP_THREADS 1024
 #define RCD_MW_MAX 32        // most workgroups that share one class in the multi-workgroup step loops
-#define RCD_MW_INTS 1024     // ints of a class's exchange area for those loops (layout: MW_* below)
+#define RCD_MW_INTS 2048     // ints of a class's exchange area for those loops (layout: MW_* below)
 
 // The stored-S sweep kernel exists for these numbers of evaluated blocks; a sweep of nneed blocks runs
 // the smallest variant that holds them and stages that many coverage vectors (the spare slots repeat the
@@ -86,8 +86,10 @@ struct RcdClass {
 
 // Exchange area of the multi-workgroup step loops, in ints from RcdClass::mwbuf (zeroed when a call starts).
 enum {
-    MW_SLOT = 16,                                // 2 banks x RCD_MW_MAX slots x 4 ints: a workgroup's post and its tag
-    MW_PEND = MW_SLOT + 2 * 4 * RCD_MW_MAX,      // RCD_KMAX x RCD_MW_MAX: segment lengths of block k's pending list
+    MW_SLOT = 16,                                // 2 banks x RCD_MW_MAX slots x 16 ints: a workgroup's post (four pieces
+                                                 // of three ints and a tag: the post proper, then up to three list entries)
+    MW_SLOT_INTS = 16,
+    MW_PEND = MW_SLOT + 2 * MW_SLOT_INTS * RCD_MW_MAX,   // RCD_KMAX x RCD_MW_MAX: segment lengths of block k's pending list
     MW_END = MW_PEND + RCD_KMAX * RCD_MW_MAX
 };
 static_assert(MW_END <= RCD_MW_INTS, "exchange area too small");
