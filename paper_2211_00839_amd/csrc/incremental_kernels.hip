@@ -432,10 +432,12 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
         inc_wave_best(key, bv);
         if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
         __syncthreads();
-        key = sh.wkey[0];
-        bv = sh.wv[0];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) inc_better(key, bv, sh.wkey[w], sh.wv[w]);
+        // every wave takes the waves' results one per lane and reduces them again: one read of LDS and three wave
+        // reductions instead of a chain over NW entries
+        static_assert((NW & (NW - 1)) == 0 && NW <= 64, "a lane per wave");
+        key = sh.wkey[lane & (NW - 1)];
+        bv = sh.wv[lane & (NW - 1)];
+        inc_wave_best(key, bv);
         best = inc_value(key);
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }          // no candidate left (cannot happen while t < total <= n)
@@ -668,10 +670,12 @@ rcd_k_gc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int 
         inc_wave_best(key, bv);
         if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
         __syncthreads();
-        key = sh.wkey[0];
-        bv = sh.wv[0];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) inc_better(key, bv, sh.wkey[w], sh.wv[w]);
+        // every wave takes the waves' results one per lane and reduces them again: one read of LDS and three wave
+        // reductions instead of a chain over NW entries
+        static_assert((NW & (NW - 1)) == 0 && NW <= 64, "a lane per wave");
+        key = sh.wkey[lane & (NW - 1)];
+        bv = sh.wv[lane & (NW - 1)];
+        inc_wave_best(key, bv);
         best = inc_value(key);
         const int vstar = bv;
         if (vstar >= n) { done = 1; break; }

@@ -305,10 +305,12 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
         inc_wave_best(key, bv);
         if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
         __syncthreads();
-        key = sh.wkey[0];
-        bv = sh.wv[0];
-#pragma unroll
-        for (int i = 1; i < NW; ++i) inc_better(key, bv, sh.wkey[i], sh.wv[i]);
+        // every wave takes the waves' results one per lane and reduces them again: one read of LDS and three wave
+        // reductions instead of a chain over NW entries
+        static_assert((NW & (NW - 1)) == 0 && NW <= 64, "a lane per wave");
+        key = sh.wkey[lane & (NW - 1)];
+        bv = sh.wv[lane & (NW - 1)];
+        inc_wave_best(key, bv);
         if (!mw_best_of_class(bar, ms, key, bv)) { alive = false; break; }
         best = inc_value(key);
         const int vstar = bv;
@@ -577,10 +579,12 @@ rcd_k_gc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, c
         inc_wave_best(key, bv);
         if (lane == 0) { sh.wkey[wave] = key; sh.wv[wave] = bv; }
         __syncthreads();
-        key = sh.wkey[0];
-        bv = sh.wv[0];
-#pragma unroll
-        for (int i = 1; i < NW; ++i) inc_better(key, bv, sh.wkey[i], sh.wv[i]);
+        // every wave takes the waves' results one per lane and reduces them again: one read of LDS and three wave
+        // reductions instead of a chain over NW entries
+        static_assert((NW & (NW - 1)) == 0 && NW <= 64, "a lane per wave");
+        key = sh.wkey[lane & (NW - 1)];
+        bv = sh.wv[lane & (NW - 1)];
+        inc_wave_best(key, bv);
         if (!mw_best_of_class(bar, ms, key, bv)) { alive = false; break; }
         best = inc_value(key);
         const int vstar = bv;
