@@ -494,9 +494,9 @@ struct Lane {
                                         : reinterpret_cast<const void *>(rcd_k_inc_steps_mw);
             HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kfn, RCD_STEP_THREADS, 0));
             const int capacity = std::max(per_cu, 0) * cu_count();
-            // (measured on one 50 000-sample class: graph cut 1418 ms with one workgroup, 537 / 408 / 374 / 411 ms with
-            // 4 / 8 / 16 / 32: past 16 the barrier's arrivals cost more than the shorter slices save)
-            const int w_max = std::min(env_int("RCD_MW_MAX_WGS", 16, 1, RCD_MW_MAX), capacity / std::max(ncls, 1));
+            // (measured on one 50 000-sample class: graph cut 1418 ms with one workgroup, 260 / 236 / 228 / 225 ms with
+            // 12 / 16 / 24 / 32; incremental gains 627 / 599 / 586 / 590 ms)
+            const int w_max = std::min(env_int("RCD_MW_MAX_WGS", 24, 1, RCD_MW_MAX), capacity / std::max(ncls, 1));
             const int mw_slice = env_int("RCD_MW_SLICE", 2048, 256, 1 << 20) / 256 * 256;    // samples a workgroup owns, at least
             if (w_max >= 2) {
                 std::vector<RcdWg> map;
