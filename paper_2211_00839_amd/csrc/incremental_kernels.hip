@@ -539,26 +539,52 @@ rcd_k_inc_steps(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, int
         } else if (nd > 0) {
             __syncthreads();       // the short list is complete in LDS
             double *gj = G + (size_t)js * ld;
-            for (int v0 = tid * 4; v0 < ld; v0 += NT * 4) {
-                double acc[4] = {0.0, 0.0, 0.0, 0.0};
-                // eight rows in flight at a time (the loads of a batch are independent of one another)
-                for (int e0 = 0; e0 < nd; e0 += 8) {
-                    f32x4 m[8];
+            // A thread's candidates in a stretch of NT * 5 samples: four in a row at 4 tid, and sample NT * 4 + tid,
+            // so that a class of up to 5120 samples is one stretch and a list of up to eight rows one trip to
+            // memory (in stretches of NT * 4 the last 1024 samples of such a class cost every step a second trip).
+            for (int sb = 0; sb < ld; sb += NT * 5) {
+                const int vv = sb + tid * 4;               // ld is a multiple of 4: a piece is whole or absent
+                const int vx = sb + NT * 4 + tid;
+                const bool piece = vv < ld, single = vx < ld;
+                if (!piece && !single) continue;
+                // (what a thread has no use for is loaded from the stretch's first sample)
+                const int pv = piece ? vv : sb, px = single ? vx : sb;
+                double acc[4] = {0.0, 0.0, 0.0, 0.0}, accx = 0.0;
+                // U rows of the list from e0 on, all requested before the first is used; past the list's end its last
+                // row again (every register is defined on every path).  The list is taken eight rows at a time and
+                // its tail in the smallest of 1, 2, 4, 8 that holds it: most lists are a row or two, and every load,
+                // wanted or not, costs the compute unit's memory pipeline its turn.
+                auto rows = [&](auto u_tag, int e0) {
+                    constexpr int U = decltype(u_tag)::value;
+                    f32x4 m[U];
+                    float x[U];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (e0 + u < nd) m[u] = *(gcf32x4)(M + (size_t)sh.sj[e0 + u] * ld + v0);
+                    for (int u = 0; u < U; ++u) {
+                        const gcf32 r = M + (size_t)sh.sj[min(e0 + u, nd - 1)] * ld;
+                        m[u] = *(gcf32x4)(r + pv);
+                        x[u] = r[px];
+                    }
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
+                    for (int u = 0; u < U; ++u)
                         if (e0 + u < nd) {
                             const float cn = sh.snew[e0 + u], co = sh.sold[e0 + u];
                             acc[0] += inc_term(m[u].x, cn, co);
                             acc[1] += inc_term(m[u].y, cn, co);
                             acc[2] += inc_term(m[u].z, cn, co);
                             acc[3] += inc_term(m[u].w, cn, co);
+                            accx += inc_term(x[u], cn, co);
                         }
-                }
+                };
+                int e0 = 0;
+                for (; nd - e0 > 4; e0 += 8) rows(std::integral_constant<int, 8>{}, e0);
+                if (nd - e0 > 2) rows(std::integral_constant<int, 4>{}, e0);
+                else if (nd - e0 == 2) rows(std::integral_constant<int, 2>{}, e0);
+                else if (nd - e0 == 1) rows(std::integral_constant<int, 1>{}, e0);
+                if (piece) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) gj[v0 + c] += acc[c];
+                    for (int c = 0; c < 4; ++c) gj[vv + c] += acc[c];
+                }
+                if (single) gj[vx] += accx;
             }
         }
         if (tid == 0) {

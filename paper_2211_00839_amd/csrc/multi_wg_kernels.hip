@@ -442,45 +442,51 @@ rcd_k_inc_steps_mw(RcdClass *__restrict__ classes, RcdPlan *__restrict__ plans, 
                 __syncthreads();
             }
             double *gj = G + (size_t)js * ld;
-            // a thread's candidates: pieces of four, NT * 4 apart; two pieces are served by the same trips (a slice
-            // a little over NT * 4 samples, the usual case, is then one round instead of two)
-            for (int vv = v0 + tid * 4; vv < v1; vv += NT * 8) {
-                const int vw = vv + NT * 4;
-                const bool second = vw < v1;
-                double acc[2][4] = {{0.0, 0.0, 0.0, 0.0}, {0.0, 0.0, 0.0, 0.0}};
-                for (int e0 = 0; e0 < nd; e0 += 4) {
-                    // (every element is loaded, past the list's end from its last row and without a second piece
-                    // from the first again: a register left undefined on some path would be kept alive around the
-                    // whole step loop)
-                    f32x4 m[2][4];
+            // A thread's candidates in a stretch of NT * 5 samples of the slice: four in a row at 4 tid, and sample
+            // NT * 4 + tid (a slice a little over NT * 4 samples, the usual case, is then one stretch).
+            for (int sb = v0; sb < v1; sb += NT * 5) {
+                const int vv = sb + tid * 4;               // v1 - v0 is a multiple of 4: a piece is whole or absent
+                const int vx = sb + NT * 4 + tid;
+                const bool piece = vv < v1, single = vx < v1;
+                if (!piece && !single) continue;
+                // (what a thread has no use for is loaded from the stretch's first sample)
+                const int pv = piece ? vv : sb, px = single ? vx : sb;
+                double acc[4] = {0.0, 0.0, 0.0, 0.0}, accx = 0.0;
+                // U rows of the list from e0 on, all requested before the first is used; past the list's end its last
+                // row again (a register left undefined on some path would be kept alive around the whole step loop).
+                // The list is taken eight rows at a time and its tail in the smallest of 1, 2, 4, 8 that holds it: most
+                // lists are a row or two, and every load, wanted or not, costs the memory pipeline its turn.
+                auto rows = [&](auto u_tag, int e0) {
+                    constexpr int U = decltype(u_tag)::value;
+                    f32x4 m[U];
+                    float x[U];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
+                    for (int u = 0; u < U; ++u) {
                         const gcf32 r = M + (size_t)sh.sj[min(e0 + u, nd - 1)] * ld;
-                        m[0][u] = *(gcf32x4)(r + vv);
-                        m[1][u] = *(gcf32x4)(r + (second ? vw : vv));
+                        m[u] = *(gcf32x4)(r + pv);
+                        x[u] = r[px];
                     }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u)
+                    for (int u = 0; u < U; ++u)
                         if (e0 + u < nd) {
                             const float cn = sh.snew[e0 + u], co = sh.sold[e0 + u];
-                            acc[0][0] += inc_term(m[0][u].x, cn, co);
-                            acc[0][1] += inc_term(m[0][u].y, cn, co);
-                            acc[0][2] += inc_term(m[0][u].z, cn, co);
-                            acc[0][3] += inc_term(m[0][u].w, cn, co);
-                            if (second) {
-                                acc[1][0] += inc_term(m[1][u].x, cn, co);
-                                acc[1][1] += inc_term(m[1][u].y, cn, co);
-                                acc[1][2] += inc_term(m[1][u].z, cn, co);
-                                acc[1][3] += inc_term(m[1][u].w, cn, co);
-                            }
+                            acc[0] += inc_term(m[u].x, cn, co);
+                            acc[1] += inc_term(m[u].y, cn, co);
+                            acc[2] += inc_term(m[u].z, cn, co);
+                            acc[3] += inc_term(m[u].w, cn, co);
+                            accx += inc_term(x[u], cn, co);
                         }
-                }
+                };
+                int e0 = 0;
+                for (; nd - e0 > 4; e0 += 8) rows(std::integral_constant<int, 8>{}, e0);
+                if (nd - e0 > 2) rows(std::integral_constant<int, 4>{}, e0);
+                else if (nd - e0 == 2) rows(std::integral_constant<int, 2>{}, e0);
+                else if (nd - e0 == 1) rows(std::integral_constant<int, 1>{}, e0);
+                if (piece) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) gj[vv + c] += acc[0][c];
-                if (second) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) gj[vw + c] += acc[1][c];
+                    for (int c = 0; c < 4; ++c) gj[vv + c] += acc[c];
                 }
+                if (single) gj[vx] += accx;
             }
         }
         if (tid == 0 && w == 0) {
