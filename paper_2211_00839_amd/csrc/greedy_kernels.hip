@@ -689,13 +689,18 @@ __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsSha
     // the sweep that ran since the last call rebuilt these rows
     if (tid < d.nneed) d.valid[d.need[tid]] = 1;
     __syncthreads();
-    if (tid == 0) {
-        int m = 0;
-        for (int k = 0; k < K; ++k)
-            if (d.valid[k] && d.cnt[k] < d.cap[k]) sh.cand[m++] = k;
-        sh.ncand = m;
-        sh.nrem = 0;
-        sh.nmove = 0;
+    // the blocks that may step in this call, ascending (one lane per block and a ballot: a loop by one thread is a
+    // chain of K dependent trips to LDS)
+    static_assert(RCD_KMAX <= 64 && NW >= RCD_KMAX, "a lane per block, a wave per candidate block");
+    if (tid < 64) {
+        const bool c = tid < K && d.valid[tid] && d.cnt[tid] < d.cap[tid];
+        const unsigned long long b = __ballot(c);
+        if (c) sh.cand[__popcll(b & ((1ull << tid) - 1ull))] = tid;
+        if (tid == 0) {
+            sh.ncand = __popcll(b);
+            sh.nrem = 0;
+            sh.nmove = 0;
+        }
     }
     __syncthreads();
     const int ncand = uni(sh.ncand);
@@ -802,13 +807,16 @@ __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsSha
         for (int i0 = 0; i0 < ncand; i0 += 8) scan_all(std::integral_constant<int, 8>{}, std::integral_constant<int, 4>{}, i0);
     }
     __syncthreads();
-    if (tid < ncand) {
-        unsigned long long best = sh.wkey[tid][0];
-        int bpos = sh.wpos[tid][0];
-        for (int w = 1; w < NW; ++w)
-            if (sh.wkey[tid][w] > best) { best = sh.wkey[tid][w]; bpos = sh.wpos[tid][w]; }
-        sh.bkey[sh.cand[tid]] = best;
-        sh.bpos[sh.cand[tid]] = bpos;
+    if (wave < ncand) {
+        // wave i combines the waves' results for candidate block i, one per lane (largest key; equal keys name the
+        // same sample or no sample, so which lane's position is taken does not matter)
+        unsigned long long best = sh.wkey[wave][lane & (NW - 1)];
+        int bpos = sh.wpos[wave][lane & (NW - 1)];
+        wave_best(best, bpos);
+        if (lane == 0) {
+            sh.bkey[sh.cand[wave]] = best;
+            sh.bpos[sh.cand[wave]] = bpos;
+        }
     }
     __syncthreads();
 
@@ -865,22 +873,25 @@ __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsSha
 
     // ---- trip 3: consequences
     const int nupd = uni(sh.nrem);
-    if (tid == 0) {
-        // holes: removed positions below the new length; sources: surviving positions at or above it
-        int nm = 0, s = nR;
-        for (int i = 0; i < nupd; ++i) {
-            const int h = sh.removed[i];
-            if (h >= nR) continue;
-            for (;; ++s) {
-                bool gone = false;
-                for (int q = 0; q < nupd; ++q) gone |= sh.removed[q] == s;
-                if (!gone) break;
-            }
-            sh.hole[nm] = h;
-            sh.src[nm] = s++;
-            ++nm;
+    if (tid < 64) {
+        // holes: removed positions below the new length, in the order they were taken; sources: the surviving
+        // positions at or above it, ascending (as many as there are holes); the i-th hole is filled from the i-th
+        // source.  Lane i holds the i-th removed position and looks at position nR + i; everything else is wave
+        // operations (nupd <= K <= 64).
+        const int mine = lane < nupd ? sh.removed[lane] : -1;
+        bool gone = false;
+        for (int q = 0; q < nupd; ++q) gone |= __builtin_amdgcn_readlane(mine, q) == nR + lane;
+        const unsigned long long surv = __ballot(lane < nupd && !gone);
+        const bool hole = lane < nupd && mine < nR;
+        const unsigned long long holes = __ballot(hole);
+        if (hole) {
+            const int rank = __popcll(holes & ((1ull << lane) - 1ull));
+            unsigned long long m = surv;
+            for (int r = 0; r < rank; ++r) m &= m - 1ull;
+            sh.hole[rank] = mine;
+            sh.src[rank] = nR + (__ffsll((long long)m) - 1);
         }
-        sh.nmove = nm;
+        if (lane == 0) sh.nmove = __popcll(holes);
     }
     __syncthreads();
     const int nmove = uni(sh.nmove);
@@ -940,35 +951,40 @@ __device__ __forceinline__ void steps_rows(RcdClass &st, RcdPlan *plans, RowsSha
     // every wave is done reading cblk[] (the compaction above) before thread 0 rewrites it
     __syncthreads();
     // ---- the descriptor: what the next sweep must do, the state, the counters
-    if (tid == 0) {
-        int nneed = 0;
-        if (!done)
-            for (int k = 0; k < K; ++k)
-                if (d.cnt[k] < d.cap[k] && !d.valid[k]) d.need[nneed++] = k;
-        d.nneed = nneed;
-        if (nneed > 0) {
-            // the coverage vectors of the evaluated blocks share the sweep workgroup's LDS:
-            // the more blocks, the shorter the chunk of j one pass covers
-            int jc = rcd_sweep_chunk(nneed);
-            jc = jc > ld ? ld : jc;
-            const int C = (ld + jc - 1) / jc;
-            d.rpc = jc;
-            d.C = C;
-            for (int i = 0; i < nneed; ++i) d.cblk[d.need[i]] = C;
-            d.stat_sweeps += 1;
-            d.stat_entries += (long long)nR * n;
-            d.stat_computed += (long long)nneed * nR;
+    if (tid < 64) {
+        // the blocks whose gains the next sweep must produce, ascending (one lane per block again)
+        const bool stale = !done && tid < K && d.cnt[tid] < d.cap[tid] && !d.valid[tid];
+        const unsigned long long b = __ballot(stale);
+        const int nneed = __popcll(b);
+        // the coverage vectors of the evaluated blocks share the sweep workgroup's LDS:
+        // the more blocks, the shorter the chunk of j one pass covers
+        int jc = rcd_sweep_chunk(max(nneed, 1));
+        jc = jc > ld ? ld : jc;
+        const int C = (ld + jc - 1) / jc;
+        if (stale) {
+            d.need[__popcll(b & ((1ull << tid) - 1ull))] = tid;
+            d.cblk[tid] = C;
         }
-        d.stat_steps += t - t0;
-        d.stat_useful += useful;
-        d.nupd = nupd;
-        d.npatch = nmove;
-        d.apply_round += 1;
-        d.nR = nR;
-        d.t = t;
-        d.done = done;
-        d.stat_ticks += wall_clock64() - tick0;
-        if (done) __hip_atomic_fetch_add(&plans[0].ndone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) {
+            d.nneed = nneed;
+            if (nneed > 0) {
+                d.rpc = jc;
+                d.C = C;
+                d.stat_sweeps += 1;
+                d.stat_entries += (long long)nR * n;
+                d.stat_computed += (long long)nneed * nR;
+            }
+            d.stat_steps += t - t0;
+            d.stat_useful += useful;
+            d.nupd = nupd;
+            d.npatch = nmove;
+            d.apply_round += 1;
+            d.nR = nR;
+            d.t = t;
+            d.done = done;
+            d.stat_ticks += wall_clock64() - tick0;
+            if (done) __hip_atomic_fetch_add(&plans[0].ndone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __syncthreads();
     {
