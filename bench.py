@@ -338,7 +338,7 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the large-class similarity / recompute-sweep lines")
     ap.add_argument("--no-large", action="store_true", help="skip the whole large-class workload (200 GB of workspace)")
     ap.add_argument("--no-per-config", action="store_true", help="skip the wall times of the other workloads")
-    ap.add_argument("--only", default="", choices=["", "similarity", "similarity_full", "bandwidth", "recompute",
+    ap.add_argument("--only", default="", choices=["", "large_workload", "similarity", "similarity_full", "bandwidth", "recompute",
                                                    "stored_sweep"],
                     help="run only this kernel of the large-class shape (50 000 x 2048 bf16), for a profiler")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -368,6 +368,9 @@ def main():
         print(json.dumps({"calibration": "4 device copies of 1 GiB: each reads 2^30 B and writes 2^30 B"}))
         return
 
+    if args.only == "large_workload":
+        print(json.dumps({"large_workload_incremental": large_workload(rcd, si, torch)}))
+        return
     if args.only:
         print(json.dumps(extra_kernels(rcd, si, torch, only=args.only)))
         return
