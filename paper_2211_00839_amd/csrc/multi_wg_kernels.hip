@@ -9,8 +9,9 @@
 // step is small: each workgroup's best candidate (16 bytes), and for the incremental route the
 // entries (j, old, new) of the coverage update, which every workgroup needs for its own candidates.
 // Those go through device-scope stores and loads; the phases of a step are separated by an exchange
-// among the class's W workgroups (every workgroup posts 16 bytes and polls until it has read everybody's
-// post for that exchange: see MwExchange), which is the step's barrier and carries its payload at once.
+// among the class's W workgroups (every workgroup posts 16 bytes, and with them a list segment of up to three
+// entries, and polls until it has read everybody's post for that exchange: see MwExchange), which is the step's
+// barrier and carries its payload at once; longer segments are fetched from memory after the exchange.
 //
 // Every wait is bounded: a workgroup that has waited longer than `spin_ticks` (100 MHz ticks) raises
 // plans[0].bad = 2 and every workgroup, seeing it, leaves its loop; the kernel always exits and the
