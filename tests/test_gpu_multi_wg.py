@@ -145,3 +145,20 @@ def test_a_barrier_wait_that_runs_out_is_reported_and_every_kernel_exits(rcd, mo
     a, o, f = run(rcd, monkeypatch, S, cap, route, shared=True)
     res = oracle.lockstep(S, cap, o, a, rel_tol=1e-5, objective="gc" if route == "gc" else "fl")
     assert res["rc"] == 0 and res["checked"] == 2000, res
+
+
+@pytest.mark.parametrize("route", ["inc", "gc"])
+def test_thirty_two_workgroups_per_class(rcd, monkeypatch, route):
+    # the most workgroups a class can have (the polling wave holds one post per lane, 32 of them here), on a class
+    # of 33 slices of 256 samples; same bits as one workgroup, sampled steps refereed by the oracle
+    n = 8300
+    S = mixture_S(33, n)
+    cap = oracle.quota(n, [1, 2, 1, 3, 1])
+    monkeypatch.setenv("RCD_MW_MAX_WGS", "32")
+    a1, o1, f1 = run(rcd, monkeypatch, S, cap, route, shared=True, slice_=256)
+    a0, o0, f0 = run(rcd, monkeypatch, S, cap, route, shared=False)
+    assert np.array_equal(a1, a0) and np.array_equal(o1, o0) and np.array_equal(f1, f0)
+    objective = "gc" if route == "gc" else "fl"
+    steps = [0, 1, 4, 5, 6, 100, 2000, 4150, 8000, 8298, 8299]
+    res = oracle.lockstep(S, cap, o1, a1, rel_tol=1e-5, objective=objective, check=steps)
+    assert res["rc"] == 0 and res["checked"] == len(steps), res
