@@ -511,7 +511,7 @@ def main():
             out["extra"]["large_workload_incremental"] = large_workload(rcd, si, torch)
     if not args.no_cpu_baseline:
         n0 = int(counts[0])
-        out["cpu_baseline"] = cpu_baseline(ds, budget_steps=min(96, n0))
+        out["cpu_baseline"] = cpu_baseline(ds, budget_steps=min(320, n0))
     print(json.dumps(out))
 
 
