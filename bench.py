@@ -226,6 +226,19 @@ def one_config(rcd, si, torch, name, steps, warmup):
                       "partition_wall_time_ms": 1e3 * sec, "useful_evals_per_s": st["useful_evals"] / sec,
                       "greedy_steps": st["steps"], "sweeps": st["sweeps"], "kernel_launches": st["launches"],
                       "similarity_entries_read": st["entries_streamed"], "computed_evals": st["computed_evals"]}
+    # the other two routes, one timed pass each after one warm-up: S rebuilt inside every sweep (nothing stored),
+    # and Algorithm 1 with the graph-cut function of Section 4 on the stored S
+    for label, kwargs, route in (("recompute_route", dict(mode=rcd.MODE_RECOMPUTE), "RCD_MODE_RECOMPUTE (S tiles rebuilt by the matrix cores inside every gain sweep)"),
+                                 ("graph_cut_route", dict(mode=rcd.MODE_STORED, graph_cut=True), "rcd_partition_dataset_graph_cut (stored S)")):
+        rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, workspace=ws, **kwargs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, workspace=ws, **kwargs)
+        torch.cuda.synchronize()
+        sec = time.perf_counter() - t0
+        st = rcd.last_stats()
+        out[label] = {"route": route, "partition_wall_time_ms": 1e3 * sec, "greedy_steps": st["steps"],
+                      "useful_evals_per_s": st["useful_evals"] / sec, "runs_timed": 1}
     # instrumented pass of the sweep route: the sweep kernel at this workload's K
     rcd.profile(True)
     rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, rcd.MODE_STORED, ws)
@@ -472,6 +485,17 @@ def main():
         "bound": "latency of one workgroup's step (scan, two barriers, one row): classes run side by side, one compute unit each",
     }
 
+    # the same workload with nothing stored: S tiles rebuilt by the matrix cores inside every gain sweep (one timed pass)
+    torch.cuda.synchronize()
+    t4 = time.perf_counter()
+    rcd.partition_dataset(X, labels, ds.L, ds.r, ds.sigma2, rcd.MODE_RECOMPUTE, ws)
+    torch.cuda.synchronize()
+    rc_ms = 1e3 * (time.perf_counter() - t4)
+    rstats = rcd.last_stats()
+    recompute = {"route": "RCD_MODE_RECOMPUTE on the same workload, one timed pass", "ms_per_step": rc_ms,
+                 "value": rstats["useful_evals"] / (rc_ms * 1e-3), "unit": "gain-evals/s", "greedy_steps": rstats["steps"],
+                 "kernel_launches": rstats["launches"], "runs_timed": 1}
+
     out = {
         "metric": "marginal-gain evals/sec (gain evaluations Algorithm 1 consumes / whole-job wall time)",
         "value": value,
@@ -498,6 +522,7 @@ def main():
         "roofline": roofline,
         "incremental_route": incremental,
         "graph_cut_route": graph_cut,
+        "recompute_route": recompute,
     }
     if not args.scale and not args.no_per_config:
         # the other workloads of the configuration list (the large one is under `extra`)
